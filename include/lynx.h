@@ -1,0 +1,191 @@
+/*
+ * lynx.h - C ABI of the per-layer recompute-and-backward library for one
+ * tensor-parallel shard of a GPT transformer block on one MI355X (gfx950).
+ *
+ * The paper (Lynx, arXiv 2406.08756) schedules which operator outputs of a
+ * layer stay resident after the forward pass and where the discarded ones are
+ * regenerated (Sec. 4.2 "Problem definition": Boolean S_i per operator,
+ * recompute phases 1..5).  This library is the GPU-side mechanism under that
+ * policy: a forward that keeps or drops each named activation, a recompute
+ * call that regenerates a set of operators (one phase's segment), and a
+ * backward that regenerates on demand whatever is still missing (phase 5,
+ * the critical path) and then differentiates the layer.
+ *
+ * The layer is a chain of 13 operators; A_i is OP_i's output:
+ *   A0 X (input)     A1 Y1=LN1(X)       A2 QKV=Y1 Wqkv^T+bqkv   A3 S=Q K^T
+ *   A4 P=softmax     A5 Pd=dropout(P)   A6 C=Pd V               A7 O=C Wo^T
+ *   A8 X2=X+drop(O+bo)  A9 Y2=LN2(X2)   A10 U=Y2 W1^T+b1        A11 G=gelu(U)
+ *   A12 V2=G W2^T    A13 OUT=X2+drop(V2+b2)
+ * Bit i of a retain mask is S_i; bit i of a segment mask means "run OP_i".
+ *
+ * General rules
+ *  - Every pointer named "device" is device memory on the current HIP device,
+ *    16-byte aligned; everything else is host memory.
+ *  - The library never allocates or frees device memory and never
+ *    synchronises: all work is enqueued on the caller's stream (a hipStream_t
+ *    passed as void*; NULL is the default stream).
+ *  - All argument checking happens on the host before anything is launched;
+ *    a call that returns an error other than LYNX_ERR_HIP has launched nothing
+ *    and changed no state.  After LYNX_ERR_HIP call lynx_layer_reset.
+ *  - Tensors are row-major.  Tokens are batch-major (t = bi*seq + i).  QKV
+ *    columns are ordered [q|k|v][head][head_dim].  Weights are [out, in].
+ *    S, P, Pd are [micro_batch, local_heads, seq, seq]; only j <= i is defined
+ *    for causal layers.
+ *  - A handle is not thread-safe; distinct handles are independent.
+ */
+#ifndef LYNX_H
+#define LYNX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lynx_layer_s* lynx_layer_t; /* opaque, library-owned (host) */
+
+typedef enum {
+  LYNX_OK = 0,
+  LYNX_ERR_INVALID_ARG = 1, /* null/misaligned pointer, bad enum, bad mask */
+  LYNX_ERR_SHAPE = 2,       /* dimension not supported (see lynx_layer_config) */
+  LYNX_ERR_STATE = 3,       /* call order violated */
+  LYNX_ERR_DEPENDENCY = 4,  /* segment names an operator whose input is absent */
+  LYNX_ERR_OOM = 5,         /* workspace too small */
+  LYNX_ERR_HIP = 6          /* a HIP call or kernel launch failed */
+} lynx_status;
+
+typedef enum { LYNX_F32 = 0, LYNX_BF16 = 1 } lynx_dtype;
+
+/* Shape and constants of one shard.  Constraints (else LYNX_ERR_SHAPE):
+ * hidden, head_dim, local_ffn, seq multiples of 8; all sizes > 0;
+ * 0 <= dropout_p < 1; 0 <= tp_rank < tp_size; layer_id < 2^30; causal == 1. */
+typedef struct {
+  int32_t dtype;       /* lynx_dtype: storage type of activations, params, grads */
+  int32_t hidden;      /* h */
+  int32_t local_heads; /* a: attention heads on this rank */
+  int32_t head_dim;    /* d */
+  int32_t local_ffn;   /* f: FFN columns on this rank */
+  int32_t seq;         /* s */
+  int32_t micro_batch; /* b */
+  int32_t tp_size;     /* tensor-parallel group size (only indexes dropout) */
+  int32_t tp_rank;
+  int32_t causal;
+  float dropout_p;     /* same p at all three dropout sites */
+  float ln_eps;
+  uint64_t seed;       /* Philox key */
+  uint32_t layer_id;   /* enters the Philox counter */
+  uint32_t reserved;   /* must be 0 */
+} lynx_layer_config;
+
+/* Device pointers to the parameters, borrowed until the next set_params or
+ * destroy.  Shapes: wqkv [3*a*d, h], bqkv [3*a*d], wo [h, a*d], bo [h],
+ * w1 [f, h], b1 [f], w2 [h, f], b2 [h], LayerNorm g1, be1, g2, be2 [h]. */
+typedef struct {
+  const void *wqkv, *bqkv, *wo, *bo, *w1, *b1, *w2, *b2, *g1, *be1, *g2, *be2;
+} lynx_params;
+
+/* Device pointers to caller-owned gradient buffers of the same shapes and
+ * dtype as the parameters; each is overwritten (not accumulated into). */
+typedef struct {
+  void *wqkv, *bqkv, *wo, *bo, *w1, *b1, *w2, *b2, *g1, *be1, *g2, *be2;
+} lynx_grads;
+
+/* Retain-mask presets (Sec. 2.2 of the paper: Full Recomputation keeps only
+ * the layer input; Selective Recomputation drops the attention operators'
+ * seq x seq tensors).  Bits 0 and 13 are always treated as set. */
+#define LYNX_RETAIN_STORE_ALL 0x3FFFu
+#define LYNX_RETAIN_FULL_RECOMPUTE 0x2001u
+#define LYNX_RETAIN_ATTENTION_ONLY (0x3FFFu & ~0x0038u)   /* drop S, P, Pd */
+#define LYNX_RETAIN_ELEMENTWISE_ONLY (0x3FFFu & ~0x0830u) /* drop P, Pd, G */
+/* Segment meaning "whatever backward still needs, with its missing ancestors" */
+#define LYNX_SEG_ALL_MISSING 0xFFFFFFFFu
+
+#define LYNX_NUM_ACTIVATIONS 14
+
+/* M_i of the paper's memory constraint (Eq. 8): bytes of activation act_id
+ * (0..13) for this shape.  LayerNorm outputs (A1, A9) include their two fp32
+ * per-token statistics.  Returns 0 for a bad argument. */
+size_t lynx_activation_bytes(const lynx_layer_config* cfg, int act_id);
+
+/* Workspace (device bytes) that lynx_layer_create needs so that
+ * forward(retain_mask) -> [recompute(ALL_MISSING)] -> backward fits, including
+ * all transient buffers.  Found by replaying that call sequence against the
+ * library's own (deterministic, first-fit) allocator without launching
+ * anything, so it is exact for that sequence.  Explicit segments issued in
+ * another order place buffers differently and can need more; a planner can
+ * rehearse any sequence with lynx_layer_set_dry_run and read
+ * lynx_layer_peak_bytes.  0 on a bad config. */
+size_t lynx_workspace_bytes(const lynx_layer_config* cfg, uint32_t retain_mask);
+
+/* Create a layer over a caller-owned device workspace (borrowed until
+ * destroy).  Errors: INVALID_ARG (null/misaligned), SHAPE. */
+lynx_status lynx_layer_create(const lynx_layer_config* cfg, void* workspace_device,
+                              size_t workspace_bytes, lynx_layer_t* out_layer);
+lynx_status lynx_layer_destroy(lynx_layer_t layer);
+
+lynx_status lynx_layer_set_params(lynx_layer_t layer, const lynx_params* params);
+
+/* Forward pass (operators 1..13) under a retain policy: after an operator's
+ * last forward consumer has run, its output is released unless its retain bit
+ * is set.  x_device [T, h] is borrowed and must stay valid and unchanged
+ * until backward returns (it is the layer's checkpoint); out_device [T, h] is
+ * written.  `step` selects the dropout masks (the Philox counter).
+ * Errors: STATE (forward already pending), INVALID_ARG, OOM. */
+lynx_status lynx_layer_forward(lynx_layer_t layer, const void* x_device, void* out_device,
+                               uint32_t retain_mask, uint64_t step, void* hip_stream);
+
+/* Regenerate a segment: the operators named in segment_mask run in index
+ * order with the forward's kernels and launch geometry, so their outputs are
+ * bit-identical to the forward's.  An operator whose output is resident is
+ * skipped.  An operator with an absent input that no earlier operator of the
+ * segment produces fails the whole call with DEPENDENCY (Eq. 4: a parent must
+ * be stored or already regenerated).  Regenerated S, O or V2 (which backward
+ * never reads) are released again as soon as their consumers are resident.
+ * Errors: STATE (no forward pending), DEPENDENCY, OOM. */
+lynx_status lynx_recompute(lynx_layer_t layer, uint32_t segment_mask, void* hip_stream);
+
+/* Backward pass.  First regenerates everything still missing (phase 5), then
+ * computes d_x_device [T, h] and all twelve parameter gradients from
+ * d_out_device [T, h] (borrowed, read-only), releasing activations as it goes.
+ * Afterwards the layer is idle again and holds nothing.
+ * Errors: STATE, INVALID_ARG, OOM. */
+lynx_status lynx_layer_backward(lynx_layer_t layer, const void* d_out_device, void* d_x_device,
+                                const lynx_grads* grads, void* hip_stream);
+
+/* Drop all resident activations and return to idle without a backward
+ * (inference-style use, or abandoning a micro-batch). */
+lynx_status lynx_layer_reset(lynx_layer_t layer);
+
+/* Bookkeeping queries (host only, no GPU work).  live mask: bit i set iff A_i
+ * is resident (bits 0 and 13 refer to the caller's buffers).  live bytes:
+ * sum of M_i over resident A_1..A_12, i.e. sum_i S_i*M_i right after forward.
+ * peak bytes: high-water mark of the workspace since create. */
+lynx_status lynx_layer_live_mask(lynx_layer_t layer, uint32_t* live);
+lynx_status lynx_layer_live_bytes(lynx_layer_t layer, size_t* bytes);
+lynx_status lynx_layer_peak_bytes(lynx_layer_t layer, size_t* bytes);
+
+/* Device address and size of a resident activation (for parity checks); the
+ * pointer is NULL when the activation is not resident.  For A1 / A9 the
+ * statistics follow the [T, h] tensor directly: mean[T] then rstd[T], fp32. */
+lynx_status lynx_layer_activation(lynx_layer_t layer, int act_id, const void** device_ptr,
+                                  size_t* bytes);
+
+/* Write the keep-mask of one dropout site as bytes (1 = keep) for parity
+ * checks: site 0 -> [b, a, s, s] (all j, also above the diagonal), sites 1, 2
+ * -> [T, h].  Masks are a pure function of (seed, step, layer_id, site,
+ * element index) and are never stored by the library. */
+lynx_status lynx_dropout_mask(const lynx_layer_config* cfg, uint64_t step, int site,
+                              uint8_t* out_device, void* hip_stream);
+
+/* When on, calls do all host bookkeeping (allocation, residency, errors) but
+ * launch no kernel; pointers are then only checked for alignment.  Used by
+ * lynx_workspace_bytes and by planners that want a policy's memory curve. */
+lynx_status lynx_layer_set_dry_run(lynx_layer_t layer, int on);
+
+const char* lynx_status_string(lynx_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LYNX_H */

@@ -92,13 +92,32 @@ def dropout_keep(seed: int, step: int, layer_id: int, site: int,
     return u16 >= np.uint64(dropout_threshold(p))
 
 
+def dropout_keep_range(seed: int, step: int, layer_id: int, site: int,
+                       first: int, count: int, p: float) -> np.ndarray:
+    """dropout_keep for the contiguous indices first .. first+count-1, with the
+    generator evaluated once per group of 8 elements instead of once per
+    element (same values; first and count must be multiples of 8)."""
+    if first % 8 or count % 8:
+        return dropout_keep(seed, step, layer_id, site,
+                            np.arange(first, first + count, dtype=np.uint64), p)
+    n = np.arange(first // 8, (first + count) // 8, dtype=np.uint64)
+    stream = (int(step) << 32) | (int(layer_id) << 2) | int(site)
+    w = philox4x32_10(n & _LO32, n >> _SH32, stream & 0xFFFFFFFF, stream >> 32,
+                      seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    fields = np.empty((n.size, 8), dtype=np.uint64)
+    for k in range(4):
+        fields[:, 2 * k] = w[k] & np.uint64(0xFFFF)
+        fields[:, 2 * k + 1] = w[k] >> np.uint64(16)
+    return (fields >= np.uint64(dropout_threshold(p))).reshape(-1)
+
+
 def hidden_mask(cfg, step: int, site: int) -> np.ndarray:
     """Mask of a hidden-dropout site (1: after the attention projection, 2:
     after FC2), shape [T, h].  Element index t*h + j: the same on every
     tensor-parallel rank, as it must be for a tensor that follows an all-reduce."""
     T, h = cfg.micro_batch * cfg.seq, cfg.hidden
-    idx = np.arange(T * h, dtype=np.uint64).reshape(T, h)
-    return dropout_keep(cfg.seed, step, cfg.layer_id, site, idx, cfg.dropout_p)
+    return dropout_keep_range(cfg.seed, step, cfg.layer_id, site, 0, T * h,
+                              cfg.dropout_p).reshape(T, h)
 
 
 def attention_mask_slice(cfg, step: int, bi: int, hd: int) -> np.ndarray:
@@ -109,9 +128,8 @@ def attention_mask_slice(cfg, step: int, bi: int, hd: int) -> np.ndarray:
     s, a = cfg.seq, cfg.local_heads
     A = a * cfg.tp_size
     g = cfg.tp_rank * a + hd
-    base = np.uint64((bi * A + g) * s * s)
-    idx = base + np.arange(s * s, dtype=np.uint64).reshape(s, s)
-    return dropout_keep(cfg.seed, step, cfg.layer_id, 0, idx, cfg.dropout_p)
+    return dropout_keep_range(cfg.seed, step, cfg.layer_id, 0, (bi * A + g) * s * s,
+                              s * s, cfg.dropout_p).reshape(s, s)
 
 
 # --------------------------------------------------------------------------

@@ -1,0 +1,199 @@
+"""ctypes binding of liblynx.so: argument marshalling only.
+
+Function names and argument order are those of include/lynx.h.  Device
+buffers are passed as torch tensors (or raw integer addresses); torch is used
+for device memory and streams, nothing else.  There is no fallback: if the
+library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblynx.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2406_08756_amd.build` "
+        "(there is no CPU or PyTorch fallback)")
+_lib = C.CDLL(LIB_PATH)
+
+LYNX_OK, LYNX_ERR_INVALID_ARG, LYNX_ERR_SHAPE, LYNX_ERR_STATE = 0, 1, 2, 3
+LYNX_ERR_DEPENDENCY, LYNX_ERR_OOM, LYNX_ERR_HIP = 4, 5, 6
+LYNX_F32, LYNX_BF16 = 0, 1
+LYNX_RETAIN_STORE_ALL = 0x3FFF
+LYNX_RETAIN_FULL_RECOMPUTE = 0x2001
+LYNX_RETAIN_ATTENTION_ONLY = 0x3FFF & ~0x0038
+LYNX_RETAIN_ELEMENTWISE_ONLY = 0x3FFF & ~0x0830
+LYNX_SEG_ALL_MISSING = 0xFFFFFFFF
+LYNX_NUM_ACTIVATIONS = 14
+PARAM_FIELDS = ("wqkv", "bqkv", "wo", "bo", "w1", "b1", "w2", "b2", "g1", "be1", "g2", "be2")
+
+
+class lynx_layer_config(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("hidden", C.c_int32), ("local_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("local_ffn", C.c_int32), ("seq", C.c_int32),
+                ("micro_batch", C.c_int32), ("tp_size", C.c_int32), ("tp_rank", C.c_int32),
+                ("causal", C.c_int32), ("dropout_p", C.c_float), ("ln_eps", C.c_float),
+                ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class lynx_params(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
+
+
+class lynx_grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
+
+
+class LynxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lynx_status_string(status)} (status {status})")
+
+
+_cfg_p = C.POINTER(lynx_layer_config)
+_proto = {
+    "lynx_activation_bytes": (C.c_size_t, [_cfg_p, C.c_int]),
+    "lynx_workspace_bytes": (C.c_size_t, [_cfg_p, C.c_uint32]),
+    "lynx_layer_create": (C.c_int, [_cfg_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]),
+    "lynx_layer_destroy": (C.c_int, [C.c_void_p]),
+    "lynx_layer_set_params": (C.c_int, [C.c_void_p, C.POINTER(lynx_params)]),
+    "lynx_layer_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
+                                     C.c_void_p]),
+    "lynx_recompute": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p]),
+    "lynx_layer_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(lynx_grads),
+                                      C.c_void_p]),
+    "lynx_layer_reset": (C.c_int, [C.c_void_p]),
+    "lynx_layer_live_mask": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
+    "lynx_layer_live_bytes": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t)]),
+    "lynx_layer_peak_bytes": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t)]),
+    "lynx_layer_activation": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p),
+                                        C.POINTER(C.c_size_t)]),
+    "lynx_dropout_mask": (C.c_int, [_cfg_p, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p]),
+    "lynx_layer_set_dry_run": (C.c_int, [C.c_void_p, C.c_int]),
+    "lynx_status_string": (C.c_char_p, [C.c_int]),
+}
+for _name, (_res, _args) in _proto.items():
+    _f = getattr(_lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+EXPORTED = tuple(_proto)
+
+
+def _addr(buf) -> Optional[int]:
+    """Device address of a torch tensor, or an integer address passed through."""
+    if buf is None:
+        return None
+    if isinstance(buf, int):
+        return buf
+    return buf.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != LYNX_OK:
+        raise LynxError(status, where)
+
+
+def make_config(cfg) -> lynx_layer_config:
+    """From any object with the config's field names (e.g. lynx_synth.LayerConfig)."""
+    if isinstance(cfg, lynx_layer_config):
+        return cfg
+    return lynx_layer_config(int(cfg.dtype), cfg.hidden, cfg.local_heads, cfg.head_dim,
+                             cfg.local_ffn, cfg.seq, cfg.micro_batch, cfg.tp_size, cfg.tp_rank,
+                             int(cfg.causal), float(cfg.dropout_p), float(cfg.ln_eps),
+                             int(cfg.seed), int(cfg.layer_id), 0)
+
+
+def lynx_status_string(status: int) -> str:
+    return _lib.lynx_status_string(status).decode()
+
+
+def lynx_activation_bytes(cfg, act_id: int) -> int:
+    return _lib.lynx_activation_bytes(C.byref(make_config(cfg)), act_id)
+
+
+def lynx_workspace_bytes(cfg, retain_mask: int) -> int:
+    return _lib.lynx_workspace_bytes(C.byref(make_config(cfg)), retain_mask)
+
+
+def lynx_layer_create(cfg, workspace, workspace_bytes: int) -> int:
+    handle = C.c_void_p()
+    _check(_lib.lynx_layer_create(C.byref(make_config(cfg)), _addr(workspace), workspace_bytes,
+                                  C.byref(handle)), "lynx_layer_create")
+    return handle.value
+
+
+def lynx_layer_destroy(layer: int) -> None:
+    _check(_lib.lynx_layer_destroy(layer), "lynx_layer_destroy")
+
+
+def _ptr_struct(cls, tensors: Dict[str, object]):
+    return cls(*[_addr(tensors[n]) for n in PARAM_FIELDS])
+
+
+def lynx_layer_set_params(layer: int, params: Dict[str, object]) -> None:
+    st = _ptr_struct(lynx_params, params)
+    _check(_lib.lynx_layer_set_params(layer, C.byref(st)), "lynx_layer_set_params")
+
+
+def lynx_layer_forward(layer: int, x, out, retain_mask: int, step: int = 0, stream=None) -> None:
+    _check(_lib.lynx_layer_forward(layer, _addr(x), _addr(out), retain_mask, step, _stream(stream)),
+           "lynx_layer_forward")
+
+
+def lynx_recompute(layer: int, segment_mask: int, stream=None) -> None:
+    _check(_lib.lynx_recompute(layer, segment_mask, _stream(stream)), "lynx_recompute")
+
+
+def lynx_layer_backward(layer: int, d_out, d_x, grads: Dict[str, object], stream=None) -> None:
+    st = _ptr_struct(lynx_grads, grads)
+    _check(_lib.lynx_layer_backward(layer, _addr(d_out), _addr(d_x), C.byref(st), _stream(stream)),
+           "lynx_layer_backward")
+
+
+def lynx_layer_reset(layer: int) -> None:
+    _check(_lib.lynx_layer_reset(layer), "lynx_layer_reset")
+
+
+def lynx_layer_live_mask(layer: int) -> int:
+    v = C.c_uint32()
+    _check(_lib.lynx_layer_live_mask(layer, C.byref(v)), "lynx_layer_live_mask")
+    return v.value
+
+
+def lynx_layer_live_bytes(layer: int) -> int:
+    v = C.c_size_t()
+    _check(_lib.lynx_layer_live_bytes(layer, C.byref(v)), "lynx_layer_live_bytes")
+    return v.value
+
+
+def lynx_layer_peak_bytes(layer: int) -> int:
+    v = C.c_size_t()
+    _check(_lib.lynx_layer_peak_bytes(layer, C.byref(v)), "lynx_layer_peak_bytes")
+    return v.value
+
+
+def lynx_layer_activation(layer: int, act_id: int):
+    """(device address or None, bytes)."""
+    p, n = C.c_void_p(), C.c_size_t()
+    _check(_lib.lynx_layer_activation(layer, act_id, C.byref(p), C.byref(n)), "lynx_layer_activation")
+    return p.value, n.value
+
+
+def lynx_dropout_mask(cfg, step: int, site: int, out, stream=None) -> None:
+    _check(_lib.lynx_dropout_mask(C.byref(make_config(cfg)), step, site, _addr(out), _stream(stream)),
+           "lynx_dropout_mask")
+
+
+def lynx_layer_set_dry_run(layer: int, on: bool) -> None:
+    _check(_lib.lynx_layer_set_dry_run(layer, int(on)), "lynx_layer_set_dry_run")

@@ -1,0 +1,93 @@
+// Host-callable launchers of the HIP kernels.  Every launcher enqueues on the
+// given stream, never synchronises, and returns the launch status.  `dtype`
+// is 0 for fp32 storage and 1 for bf16 storage; arithmetic is fp32 throughout.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lynx {
+
+struct DropoutParams {
+  uint64_t seed;
+  uint64_t step;
+  uint32_t layer_id;
+  float p;
+};
+
+// Index map of the attention-dropout site: element (bi, hd, i, j) of a shard
+// has flat index ((bi * global_heads + head0 + hd) * s + i) * s + j.
+struct AttnShape {
+  int b, a, s;
+  int global_heads, head0;
+};
+
+// ---- LayerNorm ------------------------------------------------------------
+hipError_t layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
+                         float* mean, float* rstd, int rows, int cols, float eps, hipStream_t st);
+// dx_out = dres + dLN/dx (dres may alias nothing; dx_out may alias dres);
+// dgamma/dbeta are reduced over rows in two fixed-order stages through scratch.
+size_t layernorm_bwd_scratch_bytes(int rows, int cols);
+hipError_t layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean,
+                         const float* rstd, const void* gamma, const void* dres, void* dx_out,
+                         void* dgamma, void* dbeta, float* scratch, int rows, int cols,
+                         hipStream_t st);
+
+// ---- attention softmax / dropout -----------------------------------------
+// P = softmax_{j<=i}(S * scale) (written if P != null), Pd = keep * P * c
+// (written if Pd != null; computed from the storage-rounded P).  Columns
+// (i, round_up(i+1, 128)) of every written row are zero-filled.
+hipError_t softmax_dropout_fwd(int dtype, const void* S, void* P, void* Pd, AttnShape sh,
+                               float scale, DropoutParams dp, hipStream_t st);
+// Pd = keep * P * c from a resident P.
+hipError_t attn_dropout_fwd(int dtype, const void* P, void* Pd, AttnShape sh, DropoutParams dp,
+                            hipStream_t st);
+// dS = scale * P * (dP - sum_j dP * P), dP = keep * dPd * c; dS may alias dPd.
+hipError_t softmax_dropout_bwd(int dtype, const void* dPd, const void* P, void* dS, AttnShape sh,
+                               float scale, DropoutParams dp, hipStream_t st);
+
+// ---- elementwise over [rows, cols] -----------------------------------------
+hipError_t gelu_fwd(int dtype, const void* u, void* g, size_t n, hipStream_t st);
+size_t colsum_scratch_bytes(int rows, int cols);
+// du = dg * gelu'(u); dbias[c] = sum_r du[r, c]
+hipError_t gelu_bwd(int dtype, const void* dg, const void* u, void* du, void* dbias,
+                    float* scratch, int rows, int cols, hipStream_t st);
+// out = res + keep * (in + bias) * c, dropout site `site`, element index r*cols + c
+hipError_t bias_dropout_add_fwd(int dtype, const void* in, const void* bias, const void* res,
+                                void* out, int rows, int cols, int site, DropoutParams dp,
+                                hipStream_t st);
+// din = keep * dout * c; dbias[c] = sum_r din[r, c]
+hipError_t dropout_bwd(int dtype, const void* dout, void* din, void* dbias, float* scratch,
+                       int rows, int cols, int site, DropoutParams dp, hipStream_t st);
+// dbias[c] = sum_r x[r, c]
+hipError_t column_sum(int dtype, const void* x, void* dbias, float* scratch, int rows, int cols,
+                      hipStream_t st);
+// keep-mask bytes for parity checks: n elements starting at flat index 0 of
+// site 1/2, or the [b, a, s, s] tensor of site 0.
+hipError_t dropout_mask_hidden(uint8_t* out, size_t n, int site, DropoutParams dp, hipStream_t st);
+hipError_t dropout_mask_attn(uint8_t* out, AttnShape sh, DropoutParams dp, hipStream_t st);
+
+// ---- matrix products ------------------------------------------------------
+enum CausalMode : int {
+  kCausalNone = 0,
+  kCausalOutLower = 1,  // only outputs with n <= m are needed (others may be skipped)
+  kCausalKLeM = 2,      // contraction restricted to k <= m
+  kCausalKGeM = 3       // contraction restricted to k >= m
+};
+
+// C[z][m, n] = sum_k A[z][m, k] * B[z][k, n] (+ bias[n]), z = (z1, z2) a
+// two-level batch.  Element strides are explicit, so any operand may be a
+// transposed or column-sliced view.  Accumulation is fp32 in a fixed order.
+struct GemmDesc {
+  int M, N, K;
+  const void* A; long long a_sm, a_sk, a_sz1, a_sz2;
+  const void* B; long long b_sk, b_sn, b_sz1, b_sz2;
+  void* C; long long c_sm, c_sz1, c_sz2;  // C is row-major within a matrix (n stride 1)
+  const void* bias;                        // nullable, length N, same dtype
+  int nz1, nz2;
+  int causal;                              // CausalMode
+};
+hipError_t gemm(int dtype, const GemmDesc& d, hipStream_t st);          // picks a kernel
+hipError_t gemm_generic(int dtype, const GemmDesc& d, hipStream_t st);  // any shape, vector ALUs
+
+}  // namespace lynx

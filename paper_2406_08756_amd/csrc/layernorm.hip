@@ -1,0 +1,234 @@
+// LayerNorm forward (operators 1 and 9) and backward.  Forward: one wavefront
+// per token row, the row held in registers, two-pass mean / variance in fp32,
+// statistics written for backward.  Backward: one workgroup of four
+// wavefronts per row stream; each lane owns fixed columns so the per-column
+// sums for dgamma / dbeta accumulate in registers over the rows the workgroup
+// visits, and are then reduced over workgroups in a second fixed-order stage.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace lynx {
+namespace {
+
+constexpr int kFwdRowsPerBlock = 4;
+constexpr int kBwdThreads = 256;
+constexpr int kBwdMaxBlocks = 1024;
+
+template <typename T, int NC>
+__global__ void __launch_bounds__(kFwdRowsPerBlock* kWave)
+layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                     const T* __restrict__ beta, T* __restrict__ y, float* __restrict__ mean,
+                     float* __restrict__ rstd, int rows, int cols, float eps) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int r = blockIdx.x * kFwdRowsPerBlock + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const size_t base = static_cast<size_t>(r) * cols;
+  float v[NC][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < cols) {
+      load8(x + base + j0, v[c]);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) sum += v[c][k];
+    }
+  }
+  const float inv_n = 1.0f / static_cast<float>(cols);
+  const float mu = wave_sum(sum) * inv_n;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < cols) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        v[c][k] -= mu;
+        sq += v[c][k] * v[c][k];
+      }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(sq) * inv_n + eps);
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < cols) {
+      float g[8], b[8];
+      load8(gamma + j0, g);
+      load8(beta + j0, b);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[c][k] = g[k] * (v[c][k] * rs) + b[k];
+      store8(y + base + j0, v[c]);
+    }
+  }
+  if (lane == 0) {
+    mean[r] = mu;
+    rstd[r] = rs;
+  }
+}
+
+// Block-wide sum of two values; every thread gets both totals.
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* smem) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();  // previous use of smem is over
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    smem[w] = a;
+    smem[4 + w] = b;
+  }
+  __syncthreads();
+  a = (smem[0] + smem[1]) + (smem[2] + smem[3]);
+  b = (smem[4] + smem[5]) + (smem[6] + smem[7]);
+}
+
+template <typename T, int NC>
+__global__ void __launch_bounds__(kBwdThreads)
+layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                     const T* __restrict__ gamma, const T* dres, T* dx_out,
+                     float* __restrict__ part_dg, float* __restrict__ part_db, int rows, int cols) {
+  __shared__ float smem[8];
+  float g[NC][8], adg[NC][8], adb[NC][8];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+    if (j0 < cols) load8(gamma + j0, g[c]);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { adg[c][k] = 0.f; adb[c][k] = 0.f; }
+  }
+  const float inv_n = 1.0f / static_cast<float>(cols);
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    const size_t base = static_cast<size_t>(r) * cols;
+    const float mu = mean[r], rs = rstd[r];
+    float gd[NC][8], xh[NC][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+      if (j0 < cols) {
+        load8(dy + base + j0, gd[c]);
+        load8(x + base + j0, xh[c]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          xh[c][k] = (xh[c][k] - mu) * rs;
+          adg[c][k] += gd[c][k] * xh[c][k];
+          adb[c][k] += gd[c][k];
+          gd[c][k] *= g[c][k];
+          s1 += gd[c][k];
+          s2 += gd[c][k] * xh[c][k];
+        }
+      }
+    }
+    block_sum2(s1, s2, smem);
+    const float m1 = s1 * inv_n, m2 = s2 * inv_n;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+      if (j0 < cols) {
+        float o[8];
+        load8(dres + base + j0, o);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o[k] += rs * (gd[c][k] - m1 - xh[c][k] * m2);
+        store8(dx_out + base + j0, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+    if (j0 < cols) {
+      store8(part_dg + static_cast<size_t>(blockIdx.x) * cols + j0, adg[c]);
+      store8(part_db + static_cast<size_t>(blockIdx.x) * cols + j0, adb[c]);
+    }
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+layernorm_bwd_finalize_kernel(const float* __restrict__ part_dg, const float* __restrict__ part_db,
+                              T* __restrict__ dgamma, T* __restrict__ dbeta, int nparts, int cols) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  float a = 0.f, b = 0.f;
+  for (int r = 0; r < nparts; ++r) {
+    a += part_dg[static_cast<size_t>(r) * cols + c];
+    b += part_db[static_cast<size_t>(r) * cols + c];
+  }
+  store1(dgamma + c, a);
+  store1(dbeta + c, b);
+}
+
+int bwd_blocks(int rows) { return rows < kBwdMaxBlocks ? rows : kBwdMaxBlocks; }
+
+}  // namespace
+
+hipError_t layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
+                         float* mean, float* rstd, int rows, int cols, float eps, hipStream_t st) {
+  if (cols > 8192 || cols % 8) return hipErrorInvalidValue;
+  const dim3 grid((rows + kFwdRowsPerBlock - 1) / kFwdRowsPerBlock);
+  const dim3 block(kFwdRowsPerBlock * kWave);
+  const int nc = (cols / 8 + kWave - 1) / kWave;
+#define CALL(NC)                                                                                   \
+  if (dtype == 1)                                                                                  \
+    hipLaunchKernelGGL((layernorm_fwd_kernel<bf16_t, NC>), grid, block, 0, st,                     \
+                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(gamma),           \
+                       static_cast<const bf16_t*>(beta), static_cast<bf16_t*>(y), mean, rstd,      \
+                       rows, cols, eps);                                                           \
+  else                                                                                             \
+    hipLaunchKernelGGL((layernorm_fwd_kernel<float, NC>), grid, block, 0, st,                      \
+                       static_cast<const float*>(x), static_cast<const float*>(gamma),             \
+                       static_cast<const float*>(beta), static_cast<float*>(y), mean, rstd, rows,  \
+                       cols, eps)
+  if (nc <= 1) { CALL(1); }
+  else if (nc <= 2) { CALL(2); }
+  else if (nc <= 4) { CALL(4); }
+  else if (nc <= 6) { CALL(6); }
+  else if (nc <= 8) { CALL(8); }
+  else if (nc <= 10) { CALL(10); }
+  else if (nc <= 12) { CALL(12); }
+  else { CALL(16); }
+#undef CALL
+  return hipGetLastError();
+}
+
+size_t layernorm_bwd_scratch_bytes(int rows, int cols) {
+  return 2 * static_cast<size_t>(bwd_blocks(rows)) * cols * sizeof(float);
+}
+
+hipError_t layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean,
+                         const float* rstd, const void* gamma, const void* dres, void* dx_out,
+                         void* dgamma, void* dbeta, float* scratch, int rows, int cols,
+                         hipStream_t st) {
+  if (cols > 8192 || cols % 8) return hipErrorInvalidValue;
+  const int nb = bwd_blocks(rows);
+  float* part_dg = scratch;
+  float* part_db = scratch + static_cast<size_t>(nb) * cols;
+  const int nc = (cols / 8 + kBwdThreads - 1) / kBwdThreads;
+#define CALL(NC)                                                                                   \
+  if (dtype == 1)                                                                                  \
+    hipLaunchKernelGGL((layernorm_bwd_kernel<bf16_t, NC>), dim3(nb), dim3(kBwdThreads), 0, st,     \
+                       static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,  \
+                       static_cast<const bf16_t*>(gamma), static_cast<const bf16_t*>(dres),        \
+                       static_cast<bf16_t*>(dx_out), part_dg, part_db, rows, cols);                \
+  else                                                                                             \
+    hipLaunchKernelGGL((layernorm_bwd_kernel<float, NC>), dim3(nb), dim3(kBwdThreads), 0, st,      \
+                       static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,    \
+                       static_cast<const float*>(gamma), static_cast<const float*>(dres),          \
+                       static_cast<float*>(dx_out), part_dg, part_db, rows, cols)
+  if (nc <= 1) { CALL(1); }
+  else if (nc <= 2) { CALL(2); }
+  else if (nc <= 3) { CALL(3); }
+  else { CALL(4); }
+#undef CALL
+  const dim3 fgrid((cols + 255) / 256);
+  if (dtype == 1)
+    hipLaunchKernelGGL((layernorm_bwd_finalize_kernel<bf16_t>), fgrid, dim3(256), 0, st, part_dg,
+                       part_db, static_cast<bf16_t*>(dgamma), static_cast<bf16_t*>(dbeta), nb, cols);
+  else
+    hipLaunchKernelGGL((layernorm_bwd_finalize_kernel<float>), fgrid, dim3(256), 0, st, part_dg,
+                       part_db, static_cast<float*>(dgamma), static_cast<float*>(dbeta), nb, cols);
+  return hipGetLastError();
+}
+
+}  // namespace lynx

@@ -1,0 +1,720 @@
+// Host runtime behind the C ABI: configuration checks, the 13-operator graph,
+// residency bookkeeping over the workspace allocator, and the operator /
+// gradient sequences that enqueue the HIP kernels.
+//
+// Every state-changing call is executed twice: first as a rehearsal on a copy
+// of the bookkeeping with launching disabled (so dependency and out-of-memory
+// errors surface before anything is enqueued or changed), then for real.  The
+// allocator is deterministic, so both passes see the same offsets.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/lynx.h"
+#include "arena.h"
+#include "kernels.h"
+
+namespace {
+
+using lynx::Arena;
+using lynx::GemmDesc;
+
+constexpr int kNumAct = LYNX_NUM_ACTIVATIONS;
+constexpr int kNumOps = 13;
+
+// activations each operator reads (-1 terminated)
+constexpr int kParents[kNumOps + 1][3] = {
+    {-1, -1, -1}, {0, -1, -1}, {1, -1, -1}, {2, -1, -1}, {3, -1, -1}, {4, -1, -1}, {5, 2, -1},
+    {6, -1, -1},  {0, 7, -1},  {8, -1, -1}, {9, -1, -1}, {10, -1, -1}, {11, -1, -1}, {8, 12, -1}};
+// the last forward operator that reads each activation (0 = none)
+constexpr int kLastForwardUse[kNumAct] = {8, 2, 6, 4, 5, 6, 7, 8, 13, 10, 11, 12, 13, 0};
+// activations the backward pass reads
+constexpr uint32_t kBackwardNeeds = (1u << 0) | (1u << 1) | (1u << 2) | (1u << 4) | (1u << 5) |
+                                    (1u << 6) | (1u << 8) | (1u << 9) | (1u << 10) | (1u << 11);
+constexpr uint32_t kCallerOwned = (1u << 0) | (1u << 13);
+
+struct Dims {
+  int dtype, e;
+  int b, s, a, d, h, p, f, T;
+  size_t ss;  // b * a * s * s
+};
+
+bool make_dims(const lynx_layer_config* c, Dims* o) {
+  if (c == nullptr) return false;
+  if (c->dtype != LYNX_F32 && c->dtype != LYNX_BF16) return false;
+  if (c->hidden <= 0 || c->local_heads <= 0 || c->head_dim <= 0 || c->local_ffn <= 0 ||
+      c->seq <= 0 || c->micro_batch <= 0)
+    return false;
+  if (c->hidden % 8 || c->head_dim % 8 || c->local_ffn % 8 || c->seq % 8) return false;
+  if (c->hidden > 8192 || c->seq > 8192) return false;
+  if (!(c->dropout_p >= 0.0f && c->dropout_p < 1.0f)) return false;
+  if (!(c->ln_eps >= 0.0f)) return false;
+  if (c->tp_size <= 0 || c->tp_rank < 0 || c->tp_rank >= c->tp_size) return false;
+  if (c->layer_id >= (1u << 30) || c->causal != 1 || c->reserved != 0) return false;
+  const long long T = static_cast<long long>(c->micro_batch) * c->seq;
+  if (T > (1ll << 24)) return false;
+  o->dtype = c->dtype;
+  o->e = c->dtype == LYNX_BF16 ? 2 : 4;
+  o->b = c->micro_batch; o->s = c->seq; o->a = c->local_heads; o->d = c->head_dim;
+  o->h = c->hidden; o->p = c->local_heads * c->head_dim; o->f = c->local_ffn;
+  o->T = static_cast<int>(T);
+  o->ss = static_cast<size_t>(o->b) * o->a * o->s * o->s;
+  return true;
+}
+
+size_t act_bytes(const Dims& D, int i) {
+  const size_t th = static_cast<size_t>(D.T) * D.h * D.e;
+  const size_t stats = 2 * static_cast<size_t>(D.T) * sizeof(float);
+  switch (i) {
+    case 0: case 7: case 8: case 12: case 13: return th;
+    case 1: case 9: return th + stats;
+    case 2: return static_cast<size_t>(D.T) * 3 * D.p * D.e;
+    case 3: case 4: case 5: return D.ss * D.e;
+    case 6: return static_cast<size_t>(D.T) * D.p * D.e;
+    case 10: case 11: return static_cast<size_t>(D.T) * D.f * D.e;
+    default: return 0;
+  }
+}
+
+// Residency bookkeeping: copyable, so calls can be rehearsed.
+struct Book {
+  Arena arena;
+  bool live[kNumAct] = {};
+  size_t off[kNumAct] = {};
+  uint32_t retain = 0;
+  int state = 0;  // 0 idle, 1 forward done / backward pending
+};
+
+}  // namespace
+
+struct lynx_layer_s {
+  lynx_layer_config cfg;
+  Dims D;
+  char* base = nullptr;
+  Book book;
+  bool dry = false;
+  bool have_params = false;
+  lynx_params params{};
+  const void* x = nullptr;
+  void* out = nullptr;
+  uint64_t step = 0;
+};
+
+namespace {
+
+struct Ctx {  // one pass (rehearsal or real) of a call
+  lynx_layer_s* L;
+  Book* bk;
+  bool launch;
+  hipStream_t st;
+  hipError_t hip = hipSuccess;
+};
+
+#define LYNX_TRY(expr)                      \
+  do {                                      \
+    const lynx_status _s = (expr);          \
+    if (_s != LYNX_OK) return _s;           \
+  } while (0)
+
+#define LYNX_LAUNCH(cx, expr)                               \
+  do {                                                      \
+    if ((cx).launch) {                                      \
+      const hipError_t _e = (expr);                         \
+      if (_e != hipSuccess) { (cx).hip = _e; return LYNX_ERR_HIP; } \
+    }                                                       \
+  } while (0)
+
+char* act_ptr(const Ctx& cx, int i) {
+  if (i == 0) return const_cast<char*>(static_cast<const char*>(cx.L->x));
+  if (i == 13) return static_cast<char*>(cx.L->out);
+  return cx.L->base + cx.bk->off[i];
+}
+float* stats_ptr(const Ctx& cx, int i) {  // mean[T], rstd[T] behind Y1 / Y2
+  return reinterpret_cast<float*>(act_ptr(cx, i) + static_cast<size_t>(cx.L->D.T) * cx.L->D.h * cx.L->D.e);
+}
+
+lynx_status alloc_act(Ctx& cx, int i) {
+  if (i == 13) { cx.bk->live[13] = true; return LYNX_OK; }
+  size_t off;
+  if (!cx.bk->arena.alloc(act_bytes(cx.L->D, i), &off)) return LYNX_ERR_OOM;
+  cx.bk->off[i] = off;
+  cx.bk->live[i] = true;
+  return LYNX_OK;
+}
+void free_act(Ctx& cx, int i) {
+  if (i < 1 || i > 12 || !cx.bk->live[i]) return;
+  cx.bk->arena.release(cx.bk->off[i]);
+  cx.bk->live[i] = false;
+}
+
+struct Temp {  // transient workspace block
+  size_t off = 0;
+  bool held = false;
+};
+lynx_status alloc_temp(Ctx& cx, size_t bytes, Temp* t) {
+  if (!cx.bk->arena.alloc(bytes, &t->off)) return LYNX_ERR_OOM;
+  t->held = true;
+  return LYNX_OK;
+}
+void free_temp(Ctx& cx, Temp* t) {
+  if (t->held) cx.bk->arena.release(t->off);
+  t->held = false;
+}
+char* temp_ptr(const Ctx& cx, const Temp& t) { return cx.L->base + t.off; }
+
+lynx::DropoutParams dropout_params(const lynx_layer_s* L) {
+  return lynx::DropoutParams{L->cfg.seed, L->step, L->cfg.layer_id, L->cfg.dropout_p};
+}
+lynx::AttnShape attn_shape(const lynx_layer_s* L) {
+  return lynx::AttnShape{L->D.b, L->D.a, L->D.s, L->D.a * L->cfg.tp_size, L->cfg.tp_rank * L->D.a};
+}
+
+// ---- matrix-product descriptors -------------------------------------------
+// C[M, N] = A[M, K] * W[N, K]^T (+ bias): forward of a linear layer.
+GemmDesc linear_fwd(const void* A, const void* W, const void* bias, void* C, int M, int N, int K) {
+  GemmDesc g{};
+  g.M = M; g.N = N; g.K = K;
+  g.A = A; g.a_sm = K; g.a_sk = 1;
+  g.B = W; g.b_sk = 1; g.b_sn = K;
+  g.C = C; g.c_sm = N;
+  g.bias = bias; g.nz1 = g.nz2 = 1; g.causal = lynx::kCausalNone;
+  return g;
+}
+// dA[M, K] = dC[M, N] * W[N, K]: input gradient.
+GemmDesc linear_dgrad(const void* dC, const void* W, void* dA, int M, int N, int K) {
+  GemmDesc g{};
+  g.M = M; g.N = K; g.K = N;
+  g.A = dC; g.a_sm = N; g.a_sk = 1;
+  g.B = W; g.b_sk = K; g.b_sn = 1;
+  g.C = dA; g.c_sm = K;
+  g.nz1 = g.nz2 = 1; g.causal = lynx::kCausalNone;
+  return g;
+}
+// dW[N, K] = dC[M, N]^T * A[M, K]: weight gradient (contraction over tokens).
+GemmDesc linear_wgrad(const void* dC, const void* A, void* dW, int M, int N, int K) {
+  GemmDesc g{};
+  g.M = N; g.N = K; g.K = M;
+  g.A = dC; g.a_sm = 1; g.a_sk = N;
+  g.B = A; g.b_sk = K; g.b_sn = 1;
+  g.C = dW; g.c_sm = K;
+  g.nz1 = g.nz2 = 1; g.causal = lynx::kCausalNone;
+  return g;
+}
+
+// Batched attention products over (batch element, head).  `qkv` and `dqkv`
+// are [T, 3p] with column blocks q | k | v; sq is a [b, a, s, s] tensor.
+const char* col_block(const void* base, const Dims& D, int which) {
+  return static_cast<const char*>(base) + static_cast<size_t>(which) * D.p * D.e;
+}
+void set_batch(GemmDesc& g, const Dims& D) { g.nz1 = D.b; g.nz2 = D.a; }
+
+// out[i, j] = sum_dd x[i, dd] * y[j, dd], j <= i   (S = Q K^T, dPd = dC V^T)
+GemmDesc attn_outer(const void* x, long long ldx, const void* y, long long ldy, void* sq,
+                    const Dims& D) {
+  GemmDesc g{};
+  g.M = D.s; g.N = D.s; g.K = D.d;
+  g.A = x; g.a_sm = ldx; g.a_sk = 1; g.a_sz1 = static_cast<long long>(D.s) * ldx; g.a_sz2 = D.d;
+  g.B = y; g.b_sk = 1; g.b_sn = ldy; g.b_sz1 = static_cast<long long>(D.s) * ldy; g.b_sz2 = D.d;
+  g.C = sq; g.c_sm = D.s; g.c_sz1 = static_cast<long long>(D.a) * D.s * D.s;
+  g.c_sz2 = static_cast<long long>(D.s) * D.s;
+  set_batch(g, D);
+  g.causal = lynx::kCausalOutLower;
+  return g;
+}
+// out[i, dd] = sum_{j <= i} sq[i, j] * y[j, dd]   (C = Pd V, dQ = dS K)
+GemmDesc attn_rows(const void* sq, const void* y, long long ldy, void* out, long long ldo,
+                   const Dims& D) {
+  GemmDesc g{};
+  g.M = D.s; g.N = D.d; g.K = D.s;
+  g.A = sq; g.a_sm = D.s; g.a_sk = 1; g.a_sz1 = static_cast<long long>(D.a) * D.s * D.s;
+  g.a_sz2 = static_cast<long long>(D.s) * D.s;
+  g.B = y; g.b_sk = ldy; g.b_sn = 1; g.b_sz1 = static_cast<long long>(D.s) * ldy; g.b_sz2 = D.d;
+  g.C = out; g.c_sm = ldo; g.c_sz1 = static_cast<long long>(D.s) * ldo; g.c_sz2 = D.d;
+  set_batch(g, D);
+  g.causal = lynx::kCausalKLeM;
+  return g;
+}
+// out[j, dd] = sum_{i >= j} sq[i, j] * y[i, dd]   (dV = Pd^T dC, dK = dS^T Q)
+GemmDesc attn_cols(const void* sq, const void* y, long long ldy, void* out, long long ldo,
+                   const Dims& D) {
+  GemmDesc g{};
+  g.M = D.s; g.N = D.d; g.K = D.s;
+  g.A = sq; g.a_sm = 1; g.a_sk = D.s; g.a_sz1 = static_cast<long long>(D.a) * D.s * D.s;
+  g.a_sz2 = static_cast<long long>(D.s) * D.s;
+  g.B = y; g.b_sk = ldy; g.b_sn = 1; g.b_sz1 = static_cast<long long>(D.s) * ldy; g.b_sz2 = D.d;
+  g.C = out; g.c_sm = ldo; g.c_sz1 = static_cast<long long>(D.s) * ldo; g.c_sz2 = D.d;
+  set_batch(g, D);
+  g.causal = lynx::kCausalKGeM;
+  return g;
+}
+
+// ---- forward operators ------------------------------------------------------
+// Runs OP_i; its inputs are resident.  `fuse_dropout`: OP4 also emits Pd
+// (then OP5 is skipped by the caller); `write_p`: whether OP4 stores P.
+lynx_status run_op(Ctx& cx, int i, bool fuse_dropout = false, bool write_p = true) {
+  lynx_layer_s* L = cx.L;
+  const Dims& D = L->D;
+  const lynx_params& w = L->params;
+  const int dt = D.dtype;
+  if (i == 4 && !write_p) {
+    // P itself is not wanted: only Pd is produced
+    LYNX_TRY(alloc_act(cx, 5));
+    LYNX_LAUNCH(cx, lynx::softmax_dropout_fwd(dt, act_ptr(cx, 3), nullptr, act_ptr(cx, 5),
+                                              attn_shape(L), 1.0f / sqrtf(static_cast<float>(D.d)),
+                                              dropout_params(L), cx.st));
+    return LYNX_OK;
+  }
+  LYNX_TRY(alloc_act(cx, i));
+  switch (i) {
+    case 1:
+      LYNX_LAUNCH(cx, lynx::layernorm_fwd(dt, act_ptr(cx, 0), w.g1, w.be1, act_ptr(cx, 1),
+                                          stats_ptr(cx, 1), stats_ptr(cx, 1) + D.T, D.T, D.h,
+                                          L->cfg.ln_eps, cx.st));
+      break;
+    case 2:
+      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 1), w.wqkv, w.bqkv, act_ptr(cx, 2), D.T,
+                                                3 * D.p, D.h), cx.st));
+      break;
+    case 3:
+      LYNX_LAUNCH(cx, lynx::gemm(dt, attn_outer(col_block(act_ptr(cx, 2), D, 0), 3 * D.p,
+                                                col_block(act_ptr(cx, 2), D, 1), 3 * D.p,
+                                                act_ptr(cx, 3), D), cx.st));
+      break;
+    case 4: {
+      void* pd = nullptr;
+      if (fuse_dropout) {
+        LYNX_TRY(alloc_act(cx, 5));
+        pd = act_ptr(cx, 5);
+      }
+      LYNX_LAUNCH(cx, lynx::softmax_dropout_fwd(dt, act_ptr(cx, 3), act_ptr(cx, 4), pd,
+                                                attn_shape(L), 1.0f / sqrtf(static_cast<float>(D.d)),
+                                                dropout_params(L), cx.st));
+      break;
+    }
+    case 5:
+      LYNX_LAUNCH(cx, lynx::attn_dropout_fwd(dt, act_ptr(cx, 4), act_ptr(cx, 5), attn_shape(L),
+                                             dropout_params(L), cx.st));
+      break;
+    case 6:
+      LYNX_LAUNCH(cx, lynx::gemm(dt, attn_rows(act_ptr(cx, 5), col_block(act_ptr(cx, 2), D, 2),
+                                               3 * D.p, act_ptr(cx, 6), D.p, D), cx.st));
+      break;
+    case 7:
+      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 6), w.wo, nullptr, act_ptr(cx, 7), D.T,
+                                                D.h, D.p), cx.st));
+      break;
+    case 8:
+      LYNX_LAUNCH(cx, lynx::bias_dropout_add_fwd(dt, act_ptr(cx, 7), w.bo, act_ptr(cx, 0),
+                                                 act_ptr(cx, 8), D.T, D.h, 1, dropout_params(L),
+                                                 cx.st));
+      break;
+    case 9:
+      LYNX_LAUNCH(cx, lynx::layernorm_fwd(dt, act_ptr(cx, 8), w.g2, w.be2, act_ptr(cx, 9),
+                                          stats_ptr(cx, 9), stats_ptr(cx, 9) + D.T, D.T, D.h,
+                                          L->cfg.ln_eps, cx.st));
+      break;
+    case 10:
+      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 9), w.w1, w.b1, act_ptr(cx, 10), D.T,
+                                                D.f, D.h), cx.st));
+      break;
+    case 11:
+      LYNX_LAUNCH(cx, lynx::gelu_fwd(dt, act_ptr(cx, 10), act_ptr(cx, 11),
+                                     static_cast<size_t>(D.T) * D.f, cx.st));
+      break;
+    case 12:
+      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 11), w.w2, nullptr, act_ptr(cx, 12),
+                                                D.T, D.h, D.f), cx.st));
+      break;
+    case 13:
+      LYNX_LAUNCH(cx, lynx::bias_dropout_add_fwd(dt, act_ptr(cx, 12), w.b2, act_ptr(cx, 8),
+                                                 act_ptr(cx, 13), D.T, D.h, 2, dropout_params(L),
+                                                 cx.st));
+      break;
+    default:
+      return LYNX_ERR_INVALID_ARG;
+  }
+  return LYNX_OK;
+}
+
+lynx_status forward_pass(Ctx& cx, uint32_t retain) {
+  Book& bk = *cx.bk;
+  bk.retain = (retain & 0x3FFFu) | kCallerOwned;
+  bk.live[0] = true;
+  for (int i = 1; i <= kNumOps; ++i) {
+    if (i == 5) continue;  // emitted by OP4's kernel
+    if (i == 4)
+      LYNX_TRY(run_op(cx, 4, /*fuse_dropout=*/true, /*write_p=*/(bk.retain >> 4) & 1u));
+    else
+      LYNX_TRY(run_op(cx, i));
+    const int done = (i == 4) ? 5 : i;  // OP4's launch covers OP5
+    for (int j = 1; j <= 12; ++j)
+      if (bk.live[j] && kLastForwardUse[j] <= done && !((bk.retain >> j) & 1u)) free_act(cx, j);
+  }
+  bk.state = 1;
+  return LYNX_OK;
+}
+
+// Regenerated activations that backward never reads are dropped once every
+// operator that consumes them has its output resident.
+void release_stepping_stones(Ctx& cx) {
+  Book& bk = *cx.bk;
+  static const int stones[3] = {3, 7, 12};
+  for (int j : stones) {
+    if (!bk.live[j] || ((bk.retain >> j) & 1u)) continue;
+    bool all = true;
+    for (int op = 1; op <= kNumOps; ++op)
+      for (int k = 0; k < 3 && kParents[op][k] >= 0; ++k)
+        if (kParents[op][k] == j && !bk.live[op]) all = false;
+    if (all) free_act(cx, j);
+  }
+}
+
+uint32_t missing_closure(const Book& bk) {
+  uint32_t todo = 0;
+  std::vector<int> stack;
+  for (int i = 0; i < kNumAct; ++i)
+    if (((kBackwardNeeds >> i) & 1u) && !bk.live[i]) stack.push_back(i);
+  while (!stack.empty()) {
+    const int i = stack.back();
+    stack.pop_back();
+    if ((todo >> i) & 1u) continue;
+    todo |= 1u << i;
+    for (int k = 0; k < 3 && kParents[i][k] >= 0; ++k) {
+      const int j = kParents[i][k];
+      if (!bk.live[j] && !((todo >> j) & 1u)) stack.push_back(j);
+    }
+  }
+  return todo;
+}
+
+lynx_status recompute_pass(Ctx& cx, uint32_t segment) {
+  Book& bk = *cx.bk;
+  if (segment == LYNX_SEG_ALL_MISSING) segment = missing_closure(bk);
+  if (segment & ~0x3FFFu) return LYNX_ERR_INVALID_ARG;
+  // dependency rule: every input stored or produced earlier in the segment
+  {
+    bool have[kNumAct];
+    for (int i = 0; i < kNumAct; ++i) have[i] = bk.live[i];
+    for (int i = 1; i <= kNumOps; ++i) {
+      if (!((segment >> i) & 1u) || have[i]) continue;
+      for (int k = 0; k < 3 && kParents[i][k] >= 0; ++k)
+        if (!have[kParents[i][k]]) return LYNX_ERR_DEPENDENCY;
+      have[i] = true;
+    }
+  }
+  for (int i = 1; i <= kNumOps; ++i) {
+    if (!((segment >> i) & 1u) || bk.live[i]) continue;
+    if (i == 4 && ((segment >> 5) & 1u) && !bk.live[5])
+      LYNX_TRY(run_op(cx, 4, /*fuse_dropout=*/true));
+    else
+      LYNX_TRY(run_op(cx, i));
+    release_stepping_stones(cx);
+  }
+  return LYNX_OK;
+}
+
+// ---- backward ---------------------------------------------------------------
+lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grads* gr) {
+  lynx_layer_s* L = cx.L;
+  const Dims& D = L->D;
+  const lynx_params& w = L->params;
+  const int dt = D.dtype;
+  const size_t e = D.e;
+  LYNX_TRY(recompute_pass(cx, LYNX_SEG_ALL_MISSING));
+
+  const int widest = D.h > 3 * D.p ? (D.h > D.f ? D.h : D.f) : (3 * D.p > D.f ? 3 * D.p : D.f);
+  size_t scratch_bytes = lynx::colsum_scratch_bytes(D.T, widest);
+  const size_t ln_bytes = lynx::layernorm_bwd_scratch_bytes(D.T, D.h);
+  if (ln_bytes > scratch_bytes) scratch_bytes = ln_bytes;
+  Temp scratch, t_dv2, t_dg, t_du, t_dy2, t_dx2, t_do, t_dc, t_dpd, t_dqkv, t_dy1;
+  LYNX_TRY(alloc_temp(cx, scratch_bytes, &scratch));
+  float* scr = reinterpret_cast<float*>(temp_ptr(cx, scratch));
+  const size_t th = static_cast<size_t>(D.T) * D.h * e, tf = static_cast<size_t>(D.T) * D.f * e;
+
+  // B13: OUT = X2 + keep2 (V2 + b2) c
+  LYNX_TRY(alloc_temp(cx, th, &t_dv2));
+  LYNX_LAUNCH(cx, lynx::dropout_bwd(dt, d_out, temp_ptr(cx, t_dv2), gr->b2, scr, D.T, D.h, 2,
+                                    dropout_params(L), cx.st));
+  // B12: V2 = G W2^T
+  LYNX_TRY(alloc_temp(cx, tf, &t_dg));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T,
+                                              D.h, D.f), cx.st));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T,
+                                              D.h, D.f), cx.st));
+  free_temp(cx, &t_dv2);
+  free_act(cx, 11);
+  // B11: G = gelu(U)
+  LYNX_TRY(alloc_temp(cx, tf, &t_du));
+  LYNX_LAUNCH(cx, lynx::gelu_bwd(dt, temp_ptr(cx, t_dg), act_ptr(cx, 10), temp_ptr(cx, t_du),
+                                 gr->b1, scr, D.T, D.f, cx.st));
+  free_temp(cx, &t_dg);
+  free_act(cx, 10);
+  // B10: U = Y2 W1^T + b1
+  LYNX_TRY(alloc_temp(cx, th, &t_dy2));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T,
+                                              D.f, D.h), cx.st));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f,
+                                              D.h), cx.st));
+  free_temp(cx, &t_du);
+  // B9: Y2 = LN2(X2); dX2 = dOUT + dLN
+  LYNX_TRY(alloc_temp(cx, th, &t_dx2));
+  LYNX_LAUNCH(cx, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy2), act_ptr(cx, 8), stats_ptr(cx, 9),
+                                      stats_ptr(cx, 9) + D.T, w.g2, d_out, temp_ptr(cx, t_dx2),
+                                      gr->g2, gr->be2, scr, D.T, D.h, cx.st));
+  free_temp(cx, &t_dy2);
+  free_act(cx, 9);
+  free_act(cx, 8);
+  // B8: X2 = X + keep1 (O + bo) c
+  LYNX_TRY(alloc_temp(cx, th, &t_do));
+  LYNX_LAUNCH(cx, lynx::dropout_bwd(dt, temp_ptr(cx, t_dx2), temp_ptr(cx, t_do), gr->bo, scr, D.T,
+                                    D.h, 1, dropout_params(L), cx.st));
+  // B7: O = C Wo^T
+  LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * D.p * e, &t_dc));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T,
+                                              D.h, D.p), cx.st));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h,
+                                              D.p), cx.st));
+  free_temp(cx, &t_do);
+  free_act(cx, 6);
+  // B6: C = Pd V
+  LYNX_TRY(alloc_temp(cx, D.ss * e, &t_dpd));
+  LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * 3 * D.p * e, &t_dqkv));
+  char* dqkv = temp_ptr(cx, t_dqkv);
+  const char* qkv = act_ptr(cx, 2);
+  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_outer(temp_ptr(cx, t_dc), D.p, col_block(qkv, D, 2), 3 * D.p,
+                                            temp_ptr(cx, t_dpd), D), cx.st));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_cols(act_ptr(cx, 5), temp_ptr(cx, t_dc), D.p,
+                                           const_cast<char*>(col_block(dqkv, D, 2)), 3 * D.p, D),
+                             cx.st));
+  free_temp(cx, &t_dc);
+  free_act(cx, 5);
+  // B5 + B4: Pd = keep0 P c, P = softmax(S / sqrt(d)); dS overwrites dPd
+  LYNX_LAUNCH(cx, lynx::softmax_dropout_bwd(dt, temp_ptr(cx, t_dpd), act_ptr(cx, 4),
+                                            temp_ptr(cx, t_dpd), attn_shape(L),
+                                            1.0f / sqrtf(static_cast<float>(D.d)), dropout_params(L),
+                                            cx.st));
+  free_act(cx, 4);
+  // B3: S = Q K^T
+  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_rows(temp_ptr(cx, t_dpd), col_block(qkv, D, 1), 3 * D.p,
+                                           const_cast<char*>(col_block(dqkv, D, 0)), 3 * D.p, D),
+                             cx.st));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_cols(temp_ptr(cx, t_dpd), col_block(qkv, D, 0), 3 * D.p,
+                                           const_cast<char*>(col_block(dqkv, D, 1)), 3 * D.p, D),
+                             cx.st));
+  free_temp(cx, &t_dpd);
+  free_act(cx, 3);
+  // B2: QKV = Y1 Wqkv^T + bqkv
+  LYNX_TRY(alloc_temp(cx, th, &t_dy1));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
+                             cx.st));
+  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h),
+                             cx.st));
+  LYNX_LAUNCH(cx, lynx::column_sum(dt, dqkv, gr->bqkv, scr, D.T, 3 * D.p, cx.st));
+  free_temp(cx, &t_dqkv);
+  free_act(cx, 2);
+  // B1: Y1 = LN1(X); dX = dX2 + dLN
+  LYNX_LAUNCH(cx, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy1), act_ptr(cx, 0), stats_ptr(cx, 1),
+                                      stats_ptr(cx, 1) + D.T, w.g1, temp_ptr(cx, t_dx2), d_x, gr->g1,
+                                      gr->be1, scr, D.T, D.h, cx.st));
+  free_temp(cx, &t_dy1);
+  free_temp(cx, &t_dx2);
+  free_temp(cx, &scratch);
+  for (int i = 1; i <= 12; ++i) free_act(cx, i);
+  for (int i = 0; i < kNumAct; ++i) cx.bk->live[i] = false;
+  cx.bk->state = 0;
+  return LYNX_OK;
+}
+
+bool aligned16(const void* p) { return p != nullptr && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool grads_ok(const lynx_grads* g) {
+  if (g == nullptr) return false;
+  const void* const* p = reinterpret_cast<const void* const*>(g);
+  for (int i = 0; i < 12; ++i)
+    if (!aligned16(p[i])) return false;
+  return true;
+}
+
+// Rehearse on a copy, then run for real.
+template <typename F>
+lynx_status two_pass(lynx_layer_s* L, hipStream_t st, F&& body) {
+  Book copy = L->book;
+  Ctx rehearsal{L, &copy, false, st};
+  LYNX_TRY(body(rehearsal));
+  Ctx real{L, &L->book, !L->dry, st};
+  return body(real);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lynx_activation_bytes(const lynx_layer_config* cfg, int act_id) {
+  Dims D;
+  if (!make_dims(cfg, &D) || act_id < 0 || act_id >= kNumAct) return 0;
+  return act_bytes(D, act_id);
+}
+
+lynx_status lynx_layer_create(const lynx_layer_config* cfg, void* workspace, size_t workspace_bytes,
+                              lynx_layer_t* out_layer) {
+  if (cfg == nullptr || out_layer == nullptr) return LYNX_ERR_INVALID_ARG;
+  Dims D;
+  if (!make_dims(cfg, &D)) return LYNX_ERR_SHAPE;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & (Arena::kAlign - 1)))
+    return LYNX_ERR_INVALID_ARG;
+  lynx_layer_s* L = new (std::nothrow) lynx_layer_s;
+  if (L == nullptr) return LYNX_ERR_OOM;
+  L->cfg = *cfg;
+  L->D = D;
+  L->base = static_cast<char*>(workspace);
+  L->book.arena = Arena(workspace_bytes / Arena::kAlign * Arena::kAlign);
+  *out_layer = L;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_destroy(lynx_layer_t layer) {
+  if (layer == nullptr) return LYNX_ERR_INVALID_ARG;
+  delete layer;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_set_params(lynx_layer_t L, const lynx_params* params) {
+  if (L == nullptr || params == nullptr) return LYNX_ERR_INVALID_ARG;
+  const void* const* p = reinterpret_cast<const void* const*>(params);
+  for (int i = 0; i < 12; ++i)
+    if (!aligned16(p[i])) return LYNX_ERR_INVALID_ARG;
+  L->params = *params;
+  L->have_params = true;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_set_dry_run(lynx_layer_t L, int on) {
+  if (L == nullptr) return LYNX_ERR_INVALID_ARG;
+  L->dry = on != 0;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_forward(lynx_layer_t L, const void* x, void* out, uint32_t retain_mask,
+                               uint64_t step, void* hip_stream) {
+  if (L == nullptr || !aligned16(x) || !aligned16(out)) return LYNX_ERR_INVALID_ARG;
+  if (retain_mask & ~0x3FFFu) return LYNX_ERR_INVALID_ARG;
+  if (step >> 32) return LYNX_ERR_INVALID_ARG;
+  if (!L->have_params || L->book.state != 0) return LYNX_ERR_STATE;
+  const void* old_x = L->x;
+  void* old_out = L->out;
+  const uint64_t old_step = L->step;
+  L->x = x; L->out = out; L->step = step;
+  const lynx_status s = two_pass(L, static_cast<hipStream_t>(hip_stream),
+                                 [&](Ctx& cx) { return forward_pass(cx, retain_mask); });
+  if (s != LYNX_OK && s != LYNX_ERR_HIP) { L->x = old_x; L->out = old_out; L->step = old_step; }
+  return s;
+}
+
+lynx_status lynx_recompute(lynx_layer_t L, uint32_t segment_mask, void* hip_stream) {
+  if (L == nullptr) return LYNX_ERR_INVALID_ARG;
+  if (L->book.state != 1) return LYNX_ERR_STATE;
+  return two_pass(L, static_cast<hipStream_t>(hip_stream),
+                  [&](Ctx& cx) { return recompute_pass(cx, segment_mask); });
+}
+
+lynx_status lynx_layer_backward(lynx_layer_t L, const void* d_out, void* d_x, const lynx_grads* grads,
+                                void* hip_stream) {
+  if (L == nullptr || !aligned16(d_out) || !aligned16(d_x) || !grads_ok(grads))
+    return LYNX_ERR_INVALID_ARG;
+  if (L->book.state != 1) return LYNX_ERR_STATE;
+  return two_pass(L, static_cast<hipStream_t>(hip_stream),
+                  [&](Ctx& cx) { return backward_pass(cx, d_out, d_x, grads); });
+}
+
+lynx_status lynx_layer_reset(lynx_layer_t L) {
+  if (L == nullptr) return LYNX_ERR_INVALID_ARG;
+  Ctx cx{L, &L->book, false, nullptr};
+  for (int i = 1; i <= 12; ++i) free_act(cx, i);
+  for (int i = 0; i < kNumAct; ++i) L->book.live[i] = false;
+  L->book.state = 0;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_live_mask(lynx_layer_t L, uint32_t* live) {
+  if (L == nullptr || live == nullptr) return LYNX_ERR_INVALID_ARG;
+  uint32_t m = 0;
+  for (int i = 0; i < kNumAct; ++i)
+    if (L->book.live[i]) m |= 1u << i;
+  *live = m;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_live_bytes(lynx_layer_t L, size_t* bytes) {
+  if (L == nullptr || bytes == nullptr) return LYNX_ERR_INVALID_ARG;
+  size_t n = 0;
+  for (int i = 1; i <= 12; ++i)
+    if (L->book.live[i]) n += act_bytes(L->D, i);
+  *bytes = n;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_peak_bytes(lynx_layer_t L, size_t* bytes) {
+  if (L == nullptr || bytes == nullptr) return LYNX_ERR_INVALID_ARG;
+  *bytes = L->book.arena.extent_peak();
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_activation(lynx_layer_t L, int act_id, const void** device_ptr, size_t* bytes) {
+  if (L == nullptr || device_ptr == nullptr || bytes == nullptr || act_id < 0 || act_id >= kNumAct)
+    return LYNX_ERR_INVALID_ARG;
+  *bytes = act_bytes(L->D, act_id);
+  if (!L->book.live[act_id]) { *device_ptr = nullptr; return LYNX_OK; }
+  Ctx cx{L, &L->book, false, nullptr};
+  *device_ptr = act_ptr(cx, act_id);
+  return LYNX_OK;
+}
+
+size_t lynx_workspace_bytes(const lynx_layer_config* cfg, uint32_t retain_mask) {
+  Dims D;
+  if (!make_dims(cfg, &D) || (retain_mask & ~0x3FFFu)) return 0;
+  lynx_layer_s L;
+  L.cfg = *cfg;
+  L.D = D;
+  L.base = nullptr;
+  L.book.arena = Arena(static_cast<size_t>(1) << 60);
+  Ctx cx{&L, &L.book, false, nullptr};
+  lynx_grads g{};
+  if (forward_pass(cx, retain_mask) != LYNX_OK) return 0;
+  if (backward_pass(cx, nullptr, nullptr, &g) != LYNX_OK) return 0;
+  return L.book.arena.extent_peak();
+}
+
+lynx_status lynx_dropout_mask(const lynx_layer_config* cfg, uint64_t step, int site, uint8_t* out,
+                              void* hip_stream) {
+  Dims D;
+  if (cfg == nullptr || out == nullptr || site < 0 || site > 2 || (step >> 32))
+    return LYNX_ERR_INVALID_ARG;
+  if (!make_dims(cfg, &D)) return LYNX_ERR_SHAPE;
+  const lynx::DropoutParams dp{cfg->seed, step, cfg->layer_id, cfg->dropout_p};
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (site == 0)
+    e = lynx::dropout_mask_attn(out, lynx::AttnShape{D.b, D.a, D.s, D.a * cfg->tp_size,
+                                                     cfg->tp_rank * D.a}, dp, st);
+  else
+    e = lynx::dropout_mask_hidden(out, static_cast<size_t>(D.T) * D.h, site, dp, st);
+  return e == hipSuccess ? LYNX_OK : LYNX_ERR_HIP;
+}
+
+const char* lynx_status_string(lynx_status s) {
+  switch (s) {
+    case LYNX_OK: return "ok";
+    case LYNX_ERR_INVALID_ARG: return "invalid argument";
+    case LYNX_ERR_SHAPE: return "unsupported shape or configuration";
+    case LYNX_ERR_STATE: return "call order violated";
+    case LYNX_ERR_DEPENDENCY: return "recompute segment has an absent input";
+    case LYNX_ERR_OOM: return "workspace too small";
+    case LYNX_ERR_HIP: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,223 @@
+// Fused scaled, causally masked softmax with attention dropout (operators 4
+// and 5) and its backward.  One wavefront owns one row i of one (batch, head)
+// slice: the row's i+1 valid scores live in registers (16-byte vectors, lane l
+// holds vectors l, l+64, ...), reductions are wavefront butterflies, and the
+// dropout decisions are regenerated from the Philox counter, never read.
+// Written rows are zero-filled up to the next multiple of 128 columns so the
+// tensor-core attention products can read whole tiles of the diagonal blocks.
+#include "dropout_host.h"
+
+namespace lynx {
+namespace {
+
+constexpr int kRowsPerBlock = 4;  // wavefronts per workgroup
+constexpr int kPad = 128;
+
+template <typename T, int NC>
+__global__ void __launch_bounds__(kRowsPerBlock* kWave)
+softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __restrict__ Pd, int s,
+                           int a, int global_heads, int head0, float scale, DropoutKey key) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int i = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (i >= s) return;
+  const int bh = blockIdx.y;
+  const int bi = bh / a, hd = bh - bi * a;
+  const size_t row = (static_cast<size_t>(bh) * s + i) * s;
+  const uint64_t gidx = ((static_cast<uint64_t>(bi) * global_heads + head0 + hd) * s + i) *
+                        static_cast<uint64_t>(s);
+  const int nvalid = i + 1;
+  const int npad = min(s, (nvalid + kPad - 1) / kPad * kPad);
+
+  float z[NC][8];
+  float m = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < nvalid) {
+      load8(S + row + j0, z[c]);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        z[c][k] = (j0 + k < nvalid) ? z[c][k] * scale : -INFINITY;
+        m = fmaxf(m, z[c][k]);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) z[c][k] = -INFINITY;
+    }
+  }
+  m = wave_max(m);
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      z[c][k] = __expf(z[c][k] - m);  // exp(-inf) = 0 for masked entries
+      sum += z[c][k];
+    }
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < npad) {
+      float pr[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) pr[k] = round_to_storage(z[c][k] * inv, P);
+      if (P != nullptr) store8(P + row + j0, pr);
+      if (Pd != nullptr) {
+        uint32_t keep = 0;
+        if (j0 < nvalid) keep = dropout_keep8(key, (gidx + j0) >> 3);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) pr[k] = ((keep >> k) & 1u) ? pr[k] * key.scale : 0.0f;
+        store8(Pd + row + j0, pr);
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kRowsPerBlock* kWave)
+attn_dropout_fwd_kernel(const T* __restrict__ P, T* __restrict__ Pd, int s, int a, int global_heads,
+                        int head0, DropoutKey key) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int i = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (i >= s) return;
+  const int bh = blockIdx.y;
+  const int bi = bh / a, hd = bh - bi * a;
+  const size_t row = (static_cast<size_t>(bh) * s + i) * s;
+  const uint64_t gidx = ((static_cast<uint64_t>(bi) * global_heads + head0 + hd) * s + i) *
+                        static_cast<uint64_t>(s);
+  const int nvalid = i + 1;
+  const int npad = min(s, (nvalid + kPad - 1) / kPad * kPad);
+  for (int j0 = lane * 8; j0 < npad; j0 += kWave * 8) {
+    float pr[8];
+    uint32_t keep = 0;
+    if (j0 < nvalid) {
+      load8(P + row + j0, pr);
+      keep = dropout_keep8(key, (gidx + j0) >> 3);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      pr[k] = (((keep >> k) & 1u) && (j0 + k < nvalid)) ? pr[k] * key.scale : 0.0f;
+    store8(Pd + row + j0, pr);
+  }
+}
+
+template <typename T, int NC>
+__global__ void __launch_bounds__(kRowsPerBlock* kWave)
+softmax_dropout_bwd_kernel(const T* dPd, const T* __restrict__ P, T* dS,  // dS may alias dPd
+                           int s, int a, int global_heads, int head0, float scale, DropoutKey key) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int i = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (i >= s) return;
+  const int bh = blockIdx.y;
+  const int bi = bh / a, hd = bh - bi * a;
+  const size_t row = (static_cast<size_t>(bh) * s + i) * s;
+  const uint64_t gidx = ((static_cast<uint64_t>(bi) * global_heads + head0 + hd) * s + i) *
+                        static_cast<uint64_t>(s);
+  const int nvalid = i + 1;
+  const int npad = min(s, (nvalid + kPad - 1) / kPad * kPad);
+
+  float dp[NC][8], p[NC][8];
+  float dot = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < nvalid) {
+      load8(dPd + row + j0, dp[c]);
+      load8(P + row + j0, p[c]);
+      const uint32_t keep = dropout_keep8(key, (gidx + j0) >> 3);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const bool on = ((keep >> k) & 1u) && (j0 + k < nvalid);
+        dp[c][k] = on ? dp[c][k] * key.scale : 0.0f;
+        p[c][k] = (j0 + k < nvalid) ? p[c][k] : 0.0f;
+        dot += dp[c][k] * p[c][k];
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { dp[c][k] = 0.f; p[c][k] = 0.f; }
+    }
+  }
+  dot = wave_sum(dot);
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int j0 = (lane + c * kWave) * 8;
+    if (j0 < npad) {
+      float ds[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ds[k] = scale * (p[c][k] * (dp[c][k] - dot));
+      store8(dS + row + j0, ds);
+    }
+  }
+}
+
+// registers hold ceil(s / 512) vectors per lane
+#define LYNX_DISPATCH_NC(s, CALL)            \
+  if ((s) <= 512) { CALL(1); }               \
+  else if ((s) <= 1024) { CALL(2); }         \
+  else if ((s) <= 2048) { CALL(4); }         \
+  else if ((s) <= 4096) { CALL(8); }         \
+  else { CALL(16); }
+
+}  // namespace
+
+hipError_t softmax_dropout_fwd(int dtype, const void* S, void* P, void* Pd, AttnShape sh, float scale,
+                               DropoutParams dp, hipStream_t st) {
+  if (sh.s > 8192) return hipErrorInvalidValue;
+  const dim3 grid((sh.s + kRowsPerBlock - 1) / kRowsPerBlock, sh.b * sh.a);
+  const dim3 block(kRowsPerBlock * kWave);
+  const DropoutKey key = make_dropout_key(dp, 0);
+#define CALL(NC)                                                                                  \
+  if (dtype == 1)                                                                                 \
+    hipLaunchKernelGGL((softmax_dropout_fwd_kernel<bf16_t, NC>), grid, block, 0, st,              \
+                       static_cast<const bf16_t*>(S), static_cast<bf16_t*>(P),                    \
+                       static_cast<bf16_t*>(Pd), sh.s, sh.a, sh.global_heads, sh.head0, scale,    \
+                       key);                                                                      \
+  else                                                                                            \
+    hipLaunchKernelGGL((softmax_dropout_fwd_kernel<float, NC>), grid, block, 0, st,               \
+                       static_cast<const float*>(S), static_cast<float*>(P),                      \
+                       static_cast<float*>(Pd), sh.s, sh.a, sh.global_heads, sh.head0, scale, key)
+  LYNX_DISPATCH_NC(sh.s, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+hipError_t attn_dropout_fwd(int dtype, const void* P, void* Pd, AttnShape sh, DropoutParams dp,
+                            hipStream_t st) {
+  const dim3 grid((sh.s + kRowsPerBlock - 1) / kRowsPerBlock, sh.b * sh.a);
+  const dim3 block(kRowsPerBlock * kWave);
+  const DropoutKey key = make_dropout_key(dp, 0);
+  if (dtype == 1)
+    hipLaunchKernelGGL((attn_dropout_fwd_kernel<bf16_t>), grid, block, 0, st,
+                       static_cast<const bf16_t*>(P), static_cast<bf16_t*>(Pd), sh.s, sh.a,
+                       sh.global_heads, sh.head0, key);
+  else
+    hipLaunchKernelGGL((attn_dropout_fwd_kernel<float>), grid, block, 0, st,
+                       static_cast<const float*>(P), static_cast<float*>(Pd), sh.s, sh.a,
+                       sh.global_heads, sh.head0, key);
+  return hipGetLastError();
+}
+
+hipError_t softmax_dropout_bwd(int dtype, const void* dPd, const void* P, void* dS, AttnShape sh,
+                               float scale, DropoutParams dp, hipStream_t st) {
+  if (sh.s > 8192) return hipErrorInvalidValue;
+  const dim3 grid((sh.s + kRowsPerBlock - 1) / kRowsPerBlock, sh.b * sh.a);
+  const dim3 block(kRowsPerBlock * kWave);
+  const DropoutKey key = make_dropout_key(dp, 0);
+#define CALL(NC)                                                                                  \
+  if (dtype == 1)                                                                                 \
+    hipLaunchKernelGGL((softmax_dropout_bwd_kernel<bf16_t, NC>), grid, block, 0, st,              \
+                       static_cast<const bf16_t*>(dPd), static_cast<const bf16_t*>(P),            \
+                       static_cast<bf16_t*>(dS), sh.s, sh.a, sh.global_heads, sh.head0, scale,    \
+                       key);                                                                      \
+  else                                                                                            \
+    hipLaunchKernelGGL((softmax_dropout_bwd_kernel<float, NC>), grid, block, 0, st,               \
+                       static_cast<const float*>(dPd), static_cast<const float*>(P),              \
+                       static_cast<float*>(dS), sh.s, sh.a, sh.global_heads, sh.head0, scale, key)
+  LYNX_DISPATCH_NC(sh.s, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+}  // namespace lynx

@@ -1,0 +1,190 @@
+"""GPU parity: the HIP path, driven through the C ABI, against the fp64 oracle
+on the same seeded inputs.  Masks must match bit for bit; float tensors must
+satisfy max|gpu - ref| / max|ref| <= 1e-4 (fp32 storage) or 2e-2 (bf16
+storage) per tensor; regenerated activations must equal the forward's bits."""
+import numpy as np
+import pytest
+import torch
+
+import lynx_synth as synth
+from oracle import lynx_oracle as orc
+from oracle import policy_model as pm
+from harness import ACT_NAMES, GpuLayer, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
+
+SMALL = {
+    # ragged: no dimension is a multiple of a 64/128 tile
+    "ragged_f32": synth.LayerConfig(synth.F32, 72, 3, 24, 136, 40, 3, tp_size=2, tp_rank=1,
+                                    dropout_p=0.2, seed=11, layer_id=5),
+    "ragged_bf16": synth.LayerConfig(synth.BF16, 264, 3, 40, 328, 136, 2, tp_size=4, tp_rank=2,
+                                     dropout_p=0.1, seed=3, layer_id=1),
+    # several tiles of every kernel, tile-aligned
+    "tiles_bf16": synth.LayerConfig(synth.BF16, 512, 4, 128, 1024, 384, 2, tp_size=2, tp_rank=0,
+                                    dropout_p=0.1, seed=0, layer_id=2),
+    "C1": synth.CONFIGS["C1"],
+    "nodrop_bf16": synth.LayerConfig(synth.BF16, 256, 2, 64, 512, 128, 1, dropout_p=0.0),
+    "minimal_f32": synth.LayerConfig(synth.F32, 8, 1, 8, 8, 8, 1, dropout_p=0.5, seed=9),
+}
+
+
+def compare_forward(layer, acts, tol, names=None):
+    worst = {}
+    for i, name in enumerate(ACT_NAMES):
+        if i == 0 or (names and name not in names):
+            continue
+        got = layer.activation(i)
+        if got is None:
+            continue
+        ref = acts[name]
+        if i in (3, 4, 5):
+            got, ref = np.tril(got), np.tril(ref)
+        worst[name] = rel_err(got, ref)
+        assert worst[name] <= tol, (name, worst[name])
+    return worst
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_dropout_masks_bit_exact(name):
+    from paper_2406_08756_amd import binding as B
+    cfg = SMALL[name]
+    step = 3
+    T, h, b, a, s = cfg.tokens, cfg.hidden, cfg.micro_batch, cfg.local_heads, cfg.seq
+    for site in (1, 2):
+        out = torch.zeros(T * h, dtype=torch.uint8, device="cuda")
+        B.lynx_dropout_mask(cfg, step, site, out)
+        ref = orc.hidden_mask(cfg, step, site).astype(np.uint8).reshape(-1)
+        assert np.array_equal(out.cpu().numpy(), ref)
+    out = torch.zeros(b * a * s * s, dtype=torch.uint8, device="cuda")
+    B.lynx_dropout_mask(cfg, step, 0, out)
+    got = out.cpu().numpy().reshape(b, a, s, s)
+    for bi in range(b):
+        for hd in range(a):
+            assert np.array_equal(got[bi, hd], orc.attention_mask_slice(cfg, step, bi, hd).astype(np.uint8))
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_store_all_forward_and_backward_match_oracle(name):
+    cfg = SMALL[name]
+    tol = TOL[cfg.dtype]
+    params = synth.make_params(cfg, random_ln=True)
+    X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
+    acts, grads = orc.layer_forward_backward(cfg, params, X, dOUT, step=1)
+    layer = GpuLayer(cfg, params)
+    layer.forward(X, pm.STORE_ALL, step=1)
+    torch.cuda.synchronize()
+    compare_forward(layer, acts, tol)
+    for act, (mu_ref, r_ref) in ((1, (acts["mu1"], acts["rstd1"])), (9, (acts["mu2"], acts["rstd2"]))):
+        mu, r = layer.stats(act)
+        assert np.abs(mu - mu_ref).max() <= tol * max(1.0, np.abs(mu_ref).max())
+        assert rel_err(r, r_ref) <= tol
+    # the dropped entries are exactly the oracle's
+    k1 = (layer.activation(8) - X) != 0
+    assert not (k1 & ~acts["keep1"]).any()
+    layer.backward(dOUT)
+    got = layer.results()
+    for k, ref in grads.items():
+        assert rel_err(got[k], ref) <= tol, (k, rel_err(got[k], ref))
+    layer.close()
+
+
+@pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16"])
+def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
+    cfg = SMALL[name]
+    params = synth.make_params(cfg, random_ln=True)
+    X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
+    layer = GpuLayer(cfg, params, workspace_bytes=2 * GpuLayer(cfg, params).B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
+    B = layer.B
+
+    def lower(i, t):
+        if i in (3, 4, 5):
+            s = cfg.seq
+            return torch.tril(t.view(-1, s, s)).reshape(-1)
+        return t
+
+    layer.forward(X, pm.STORE_ALL, step=2)
+    torch.cuda.synchronize()
+    ref_acts = {i: lower(i, layer.activation_raw(i)) for i in range(1, 14)}
+    ref_stats = {i: layer.stats(i) for i in (1, 9)}
+    layer.backward(dOUT)
+    torch.cuda.synchronize()
+    ref_out = layer.out.clone()
+    ref_dx = layer.dx.clone()
+    ref_grads = {k: v.clone() for k, v in layer.grads.items()}
+
+    rng = np.random.default_rng(17)
+    masks = [pm.FULL_RECOMPUTE, pm.ATTENTION_ONLY, pm.ELEMENTWISE_ONLY, 1]
+    masks += [int(m) | 1 for m in rng.integers(0, 1 << 14, size=12)]
+    for n, mask in enumerate(masks):
+        layer.out.zero_(); layer.dx.zero_()
+        for v in layer.grads.values():
+            v.zero_()
+        layer.forward(X, mask, step=2)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.out, ref_out), hex(mask)
+        if n % 2 == 0:
+            # explicit regeneration: every activation backward reads is back, bit for bit
+            layer.recompute(B.LYNX_SEG_ALL_MISSING)
+            torch.cuda.synchronize()
+            live = B.lynx_layer_live_mask(layer.handle)
+            for i in pm.BACKWARD_NEEDS:
+                assert (live >> i) & 1
+                if i == 0:
+                    continue
+                assert torch.equal(lower(i, layer.activation_raw(i)), ref_acts[i]), (hex(mask), i)
+            for i in (1, 9):
+                mu, r = layer.stats(i)
+                assert np.array_equal(mu, ref_stats[i][0]) and np.array_equal(r, ref_stats[i][1])
+        layer.backward(dOUT)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.dx, ref_dx), hex(mask)
+        for k, v in layer.grads.items():
+            assert torch.equal(v, ref_grads[k]), (hex(mask), k)
+    layer.close()
+
+
+def test_explicit_segments_in_phases_then_backward():
+    """Regeneration split over several calls (the paper's phases 1-4) followed
+    by backward's on-demand remainder gives the same bits as one shot."""
+    cfg = SMALL["tiles_bf16"]
+    params = synth.make_params(cfg, random_ln=True)
+    X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
+    layer = GpuLayer(cfg, params, workspace_bytes=2 * GpuLayer(cfg, params).B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
+    B = layer.B
+    layer.forward(X, pm.STORE_ALL)
+    layer.backward(dOUT)
+    torch.cuda.synchronize()
+    ref_dx = layer.dx.clone()
+    ref_grads = {k: v.clone() for k, v in layer.grads.items()}
+    layer.forward(X, pm.FULL_RECOMPUTE)
+    with pytest.raises(B.LynxError) as e:
+        layer.recompute(1 << 6)
+    assert e.value.status == B.LYNX_ERR_DEPENDENCY
+    layer.recompute((1 << 1) | (1 << 2))            # "phase 1"
+    layer.recompute((1 << 3) | (1 << 4))            # "phase 2": P alone, S dropped again
+    assert not (B.lynx_layer_live_mask(layer.handle) >> 3) & 1
+    layer.recompute(1 << 5)                         # "phase 3": Pd from the resident P
+    layer.recompute((1 << 6) | (1 << 7) | (1 << 8)) # "phase 4"
+    layer.backward(dOUT)                            # phase 5: the rest on demand
+    torch.cuda.synchronize()
+    assert torch.equal(layer.dx, ref_dx)
+    for k, v in layer.grads.items():
+        assert torch.equal(v, ref_grads[k]), k
+    layer.close()
+
+
+def test_zero_output_projections_make_layer_identity_on_gpu():
+    cfg = SMALL["tiles_bf16"]
+    params = synth.make_params(cfg)
+    for k in ("wo", "bo", "w2", "b2"):
+        params[k] = np.zeros_like(params[k])
+    X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
+    layer = GpuLayer(cfg, params)
+    layer.forward(X, pm.FULL_RECOMPUTE)
+    layer.backward(dOUT)
+    got = layer.results()
+    assert np.array_equal(layer.out.float().cpu().numpy(), X)
+    assert np.array_equal(got["dX"], dOUT.astype(np.float64))
+    layer.close()

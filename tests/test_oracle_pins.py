@@ -76,6 +76,13 @@ def test_dropout_mask_uses_every_16bit_field_once():
         assert list(keep) == [f >= thr for f in fields]
 
 
+def test_dropout_range_form_equals_per_element_form():
+    for first, count in ((0, 64), (8 * 12345, 256), (2 ** 33 + 16, 40), (3, 21)):
+        idx = np.arange(first, first + count, dtype=np.uint64)
+        assert np.array_equal(orc.dropout_keep_range(11, 2, 5, 1, first, count, 0.3),
+                              orc.dropout_keep(11, 2, 5, 1, idx, 0.3))
+
+
 def test_dropout_mask_statistics_and_determinism():
     cfg = tiny_cfg(hidden=512, seq=64, micro_batch=4, dropout_p=0.1)
     m1 = orc.hidden_mask(cfg, 0, 1)
