@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-layer recompute-and-backward path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic micro-batch:
+lynx_layer_forward(policy) -> lynx_recompute(all missing) -> lynx_layer_backward.
+The headline value is the throughput of recompute + backward (the cost the
+paper's scheduler moves around); forward time is reported next to it.
+
+Prints ONE JSON line on stdout.  Everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+POLICIES = {"store_all": 0x3FFF, "full": 0x2001, "attention_only": 0x3FFF & ~0x0038,
+            "elementwise_only": 0x3FFF & ~0x0830}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def slot_work(cfg):
+    """Algorithmic work per kernel group: slot name -> ("mfma"|"hbm", flops or bytes)."""
+    e = 2 if cfg.dtype == 1 else 4
+    T, h, p, f, s = cfg.tokens, cfg.hidden, cfg.proj, cfg.local_ffn, cfg.seq
+    tri = cfg.micro_batch * cfg.local_heads * s * (s + 1) // 2
+    d = cfg.head_dim
+    lin = lambda n, k: 2.0 * T * n * k
+    att = 2.0 * tri * d
+    return {
+        "op1_layernorm1": ("hbm", 2 * T * h * e), "op2_qkv_gemm": ("mfma", lin(3 * p, h)),
+        "op3_scores": ("mfma", att), "op4_softmax_dropout": ("hbm", 3 * tri * e),
+        "op5_attn_dropout": ("hbm", 2 * tri * e), "op6_context": ("mfma", att),
+        "op7_attn_proj_gemm": ("mfma", lin(h, p)), "op8_bias_dropout_add1": ("hbm", 3 * T * h * e),
+        "op9_layernorm2": ("hbm", 2 * T * h * e), "op10_fc1_gemm": ("mfma", lin(f, h)),
+        "op11_gelu": ("hbm", 2 * T * f * e), "op12_fc2_gemm": ("mfma", lin(h, f)),
+        "op13_bias_dropout_add2": ("hbm", 3 * T * h * e),
+        "b13_dropout_bwd": ("hbm", 2 * T * h * e), "b12_fc2_dgrad": ("mfma", lin(h, f)),
+        "b12_fc2_wgrad": ("mfma", lin(h, f)), "b11_gelu_bwd": ("hbm", 3 * T * f * e),
+        "b10_fc1_dgrad": ("mfma", lin(f, h)), "b10_fc1_wgrad": ("mfma", lin(f, h)),
+        "b9_layernorm2_bwd": ("hbm", 4 * T * h * e), "b8_dropout_bwd": ("hbm", 2 * T * h * e),
+        "b7_proj_dgrad": ("mfma", lin(h, p)), "b7_proj_wgrad": ("mfma", lin(h, p)),
+        "b6_dpd": ("mfma", att), "b6_dv": ("mfma", att), "b54_softmax_dropout_bwd": ("hbm", 3 * tri * e),
+        "b3_dq": ("mfma", att), "b3_dk": ("mfma", att), "b2_qkv_dgrad": ("mfma", lin(3 * p, h)),
+        "b2_qkv_wgrad": ("mfma", lin(3 * p, h)), "b2_bias_grad": ("hbm", T * 3 * p * e),
+        "b1_layernorm1_bwd": ("hbm", 4 * T * h * e),
+    }
+
+
+def phase_flops(cfg, retain_mask):
+    """Algorithmic matrix-product FLOPs of forward, of the regeneration the
+    policy needs, and of backward."""
+    from oracle import policy_model as pm   # bookkeeping model only (no numerics)
+    w = slot_work(cfg)
+    op_slot = {2: "op2_qkv_gemm", 3: "op3_scores", 6: "op6_context", 7: "op7_attn_proj_gemm",
+               10: "op10_fc1_gemm", 12: "op12_fc2_gemm"}
+    fwd = sum(w[n][1] for n in op_slot.values())
+    bk = pm.LayerBookkeeping(cfg)
+    bk.forward(retain_mask)
+    rec = sum(w[op_slot[i]][1] for i in bk.recompute(pm.SEG_ALL_MISSING) if i in op_slot)
+    bwd = sum(v for n, (kind, v) in w.items() if n.startswith("b") and kind == "mfma")
+    return fwd, rec, bwd
+
+
+def cpu_baseline(cfg, retain_name):
+    """The fp64 oracle as it stands, timed on the host cores on micro-batch 1
+    (its cost is linear in the micro-batch size)."""
+    import numpy as np
+    import lynx_synth as synth
+    from oracle import lynx_oracle as orc
+    small = cfg.with_(micro_batch=1)
+    params = synth.make_params(small)
+    X, dOUT = synth.make_x(small), synth.make_dout(small)
+    t0 = time.perf_counter()
+    acts = orc.layer_forward(small, params, X)
+    t1 = time.perf_counter()
+    orc.layer_backward(small, params, acts, dOUT)
+    t2 = time.perf_counter()
+    fwd, rec, bwd = phase_flops(small, POLICIES[retain_name])
+    # the oracle has no policy machinery: regeneration costs what those forward
+    # operators cost, so scale the measured forward by the share regenerated
+    sec = (t1 - t0) * (rec / fwd) + (t2 - t1)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": (rec + bwd) / sec / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "micro_batch 1 of %d; fp64 numpy oracle forward %.1f s + backward %.1f s; "
+                      "regeneration priced as its share of forward FLOPs" % (cfg.micro_batch, t1 - t0, t2 - t1)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--policy", default=None, choices=list(POLICIES))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    import lynx_synth as synth
+    from paper_2406_08756_amd import binding as B
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    cfg = synth.CONFIGS[args.config]
+    policy = args.policy or {"C3": "elementwise_only", "C2": "full"}.get(args.config, "full")
+    mask = POLICIES[policy]
+    tdtype = torch.bfloat16 if cfg.dtype == synth.BF16 else torch.float32
+
+    def dev(a):
+        t = torch.from_numpy(a)
+        return (t.to(tdtype) if cfg.dtype == synth.BF16 else t).cuda()
+
+    log("bench: config %s policy %s; generating inputs" % (args.config, policy))
+    params = {k: dev(v) for k, v in synth.make_params(cfg).items()}
+    x, dout = dev(synth.make_x(cfg)), dev(synth.make_dout(cfg))
+    out, dx = torch.empty_like(x), torch.empty_like(x)
+    grads = {k: torch.empty_like(v) for k, v in params.items()}
+    ws_bytes = B.lynx_workspace_bytes(cfg, mask)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    layer = B.lynx_layer_create(cfg, (ws.data_ptr() + 255) // 256 * 256, ws_bytes)
+    B.lynx_layer_set_params(layer, params)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None, k=0):
+        if ev: ev[0].record(stream)
+        B.lynx_layer_forward(layer, x, out, mask, k, stream)
+        if ev: ev[1].record(stream)
+        B.lynx_recompute(layer, B.LYNX_SEG_ALL_MISSING, stream)
+        if ev: ev[2].record(stream)
+        B.lynx_layer_backward(layer, dout, dx, grads, stream)
+        if ev: ev[3].record(stream)
+
+    for k in range(args.warmup):
+        step(None, k)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k], k)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    rec_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    bwd_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+
+    # per-kernel durations: the same steps again with the library's event pairs on
+    B.lynx_layer_set_profiling(layer, True)
+    acc, cnt = {}, {}
+    def collect(prefix):
+        for name, ms in B.lynx_layer_profile_ms(layer).items():
+            key = prefix + name if name.startswith("op") else name
+            acc[key] = acc.get(key, 0.0) + ms
+            cnt[key] = cnt.get(key, 0) + 1
+
+    for k in range(args.steps):
+        B.lynx_layer_forward(layer, x, out, mask, k, stream)
+        collect("fwd/")
+        B.lynx_recompute(layer, B.LYNX_SEG_ALL_MISSING, stream)
+        B.lynx_layer_backward(layer, dout, dx, grads, stream)
+        collect("rec/")
+    B.lynx_layer_set_profiling(layer, False)
+    B.lynx_layer_destroy(layer)
+
+    work = slot_work(cfg)
+    mfma_peak = PEAK_BF16_TFLOPS if cfg.dtype == synth.BF16 else PEAK_FP32_TFLOPS
+    kernels = {}
+    for name in acc:
+        ms = acc[name] / cnt[name]
+        kind, amount = work[name.split("/")[-1]]
+        if name == "fwd/op4_softmax_dropout" and not (mask >> 4) & 1:
+            amount = amount * 2 // 3      # forward under this policy does not store P
+        if kind == "mfma":
+            ach = amount / (ms * 1e-3) / 1e12
+            kernels[name] = {"ms": round(ms, 4), "bound": "mfma", "achieved": round(ach, 2),
+                             "unit": "TFLOP/s", "frac": round(ach / mfma_peak, 4)}
+        else:
+            ach = amount / (ms * 1e-3) / 1e9
+            kernels[name] = {"ms": round(ms, 4), "bound": "hbm", "achieved": round(ach, 1),
+                             "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
+    log("%-28s %9s %6s %10s %8s" % ("kernel group", "ms", "bound", "achieved", "frac"))
+    for name, k in kernels.items():
+        log("%-28s %9.4f %6s %10.1f %8.3f" % (name, k["ms"], k["bound"], k["achieved"], k["frac"]))
+
+    # dominant kernel: the dense linear-layer products (forward, dgrad, wgrad share
+    # one kernel family); quote the one with the most time per step
+    dense = [n for n in kernels if kernels[n]["bound"] == "mfma"
+             and ("gemm" in n or n.endswith(("dgrad", "wgrad")))]
+    dom = max(dense, key=lambda n: kernels[n]["ms"])
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["achieved"], "peak": mfma_peak,
+                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": None,
+                "ms_per_launch": kernels[dom]["ms"]}
+
+    fwd_f, rec_f, bwd_f = phase_flops(cfg, mask)
+    rb_ms = rec_ms + bwd_ms
+    value = (rec_f + bwd_f) / (rb_ms * 1e-3) / 1e12
+    result = {
+        "metric": "recompute+backward TFLOP/s per GPT layer shard",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(rb_ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == synth.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": "%s: h=%d a=%d d=%d f=%d s=%d b=%d tp=%d, policy=%s" % (
+            args.config, cfg.hidden, cfg.local_heads, cfg.head_dim, cfg.local_ffn, cfg.seq,
+            cfg.micro_batch, cfg.tp_size, policy),
+            "timed_region": "lynx_recompute(all missing) + lynx_layer_backward per step, HIP events; "
+                            "each step also runs lynx_layer_forward first (forward_ms, inside wall_ms_per_step)"},
+        "recompute_ms": round(rec_ms, 4), "backward_ms": round(bwd_ms, 4), "forward_ms": round(fwd_ms, 4),
+        "wall_ms_per_step": round(wall_ms, 4),
+        "algorithmic_tflop": {"forward": fwd_f / 1e12, "recompute": rec_f / 1e12, "backward": bwd_f / 1e12},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        log("bench: timing the CPU oracle on a bounded sample")
+        result["cpu_baseline"] = cpu_baseline(cfg, policy)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -183,6 +183,20 @@ lynx_status lynx_dropout_mask(const lynx_layer_config* cfg, uint64_t step, int s
  * lynx_workspace_bytes and by planners that want a policy's memory curve. */
 lynx_status lynx_layer_set_dry_run(lynx_layer_t layer, int on);
 
+/* Per-kernel timing, the hook for the paper's Model Profiler (Sec. 3: it
+ * records each operator's execution time C_i).  While on, every kernel group
+ * the layer enqueues is bracketed by a HIP event pair on the call's stream
+ * (this adds a few microseconds per kernel, so leave it off when timing whole
+ * calls).  lynx_layer_profile_ms blocks until the recorded events complete
+ * and writes, per slot, the milliseconds of its most recent run since the
+ * previous query, or -1 if it did not run.  Slots 1..13 are the forward
+ * operators (slot 4 covers OP5 when the two run fused); the rest are the
+ * backward kernels; lynx_profile_slot_name names them ("" when unused). */
+#define LYNX_PROFILE_SLOTS 40
+lynx_status lynx_layer_set_profiling(lynx_layer_t layer, int on);
+lynx_status lynx_layer_profile_ms(lynx_layer_t layer, float* ms_out /* [LYNX_PROFILE_SLOTS], host */);
+const char* lynx_profile_slot_name(int slot);
+
 const char* lynx_status_string(lynx_status status);
 
 #ifdef __cplusplus

@@ -29,6 +29,7 @@ LYNX_RETAIN_ATTENTION_ONLY = 0x3FFF & ~0x0038
 LYNX_RETAIN_ELEMENTWISE_ONLY = 0x3FFF & ~0x0830
 LYNX_SEG_ALL_MISSING = 0xFFFFFFFF
 LYNX_NUM_ACTIVATIONS = 14
+LYNX_PROFILE_SLOTS = 40
 PARAM_FIELDS = ("wqkv", "bqkv", "wo", "bo", "w1", "b1", "w2", "b2", "g1", "be1", "g2", "be2")
 
 
@@ -74,6 +75,9 @@ _proto = {
                                         C.POINTER(C.c_size_t)]),
     "lynx_dropout_mask": (C.c_int, [_cfg_p, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p]),
     "lynx_layer_set_dry_run": (C.c_int, [C.c_void_p, C.c_int]),
+    "lynx_layer_set_profiling": (C.c_int, [C.c_void_p, C.c_int]),
+    "lynx_layer_profile_ms": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
+    "lynx_profile_slot_name": (C.c_char_p, [C.c_int]),
     "lynx_status_string": (C.c_char_p, [C.c_int]),
 }
 for _name, (_res, _args) in _proto.items():
@@ -197,3 +201,18 @@ def lynx_dropout_mask(cfg, step: int, site: int, out, stream=None) -> None:
 
 def lynx_layer_set_dry_run(layer: int, on: bool) -> None:
     _check(_lib.lynx_layer_set_dry_run(layer, int(on)), "lynx_layer_set_dry_run")
+
+
+def lynx_layer_set_profiling(layer: int, on: bool) -> None:
+    _check(_lib.lynx_layer_set_profiling(layer, int(on)), "lynx_layer_set_profiling")
+
+
+def lynx_layer_profile_ms(layer: int):
+    """{slot name: ms} for the slots that ran since the previous query."""
+    buf = (C.c_float * LYNX_PROFILE_SLOTS)()
+    _check(_lib.lynx_layer_profile_ms(layer, buf), "lynx_layer_profile_ms")
+    return {lynx_profile_slot_name(i): buf[i] for i in range(LYNX_PROFILE_SLOTS) if buf[i] >= 0}
+
+
+def lynx_profile_slot_name(slot: int) -> str:
+    return _lib.lynx_profile_slot_name(slot).decode()

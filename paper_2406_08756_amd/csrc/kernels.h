@@ -89,5 +89,7 @@ struct GemmDesc {
 };
 hipError_t gemm(int dtype, const GemmDesc& d, hipStream_t st);          // picks a kernel
 hipError_t gemm_generic(int dtype, const GemmDesc& d, hipStream_t st);  // any shape, vector ALUs
+bool gemm_mfma_supported(int dtype, const GemmDesc& d);                  // bf16, tile-aligned, unbatched
+hipError_t gemm_mfma(const GemmDesc& d, hipStream_t st);                // matrix cores
 
 }  // namespace lynx

@@ -101,6 +101,12 @@ struct lynx_layer_s {
   const void* x = nullptr;
   void* out = nullptr;
   uint64_t step = 0;
+  // optional per-kernel timing (the paper's Model Profiler collects operator
+  // execution times C_i): one begin/end event pair per slot
+  bool profiling = false;
+  hipEvent_t ev_begin[LYNX_PROFILE_SLOTS] = {};
+  hipEvent_t ev_end[LYNX_PROFILE_SLOTS] = {};
+  bool ev_recorded[LYNX_PROFILE_SLOTS] = {};
 };
 
 namespace {
@@ -119,13 +125,34 @@ struct Ctx {  // one pass (rehearsal or real) of a call
     if (_s != LYNX_OK) return _s;           \
   } while (0)
 
-#define LYNX_LAUNCH(cx, expr)                               \
-  do {                                                      \
-    if ((cx).launch) {                                      \
-      const hipError_t _e = (expr);                         \
-      if (_e != hipSuccess) { (cx).hip = _e; return LYNX_ERR_HIP; } \
-    }                                                       \
+#define LYNX_LAUNCH(cx, slot, expr)                                            \
+  do {                                                                         \
+    if ((cx).launch) {                                                         \
+      lynx_layer_s* _L = (cx).L;                                               \
+      if (_L->profiling) (void)hipEventRecord(_L->ev_begin[slot], (cx).st);    \
+      const hipError_t _e = (expr);                                            \
+      if (_e != hipSuccess) { (cx).hip = _e; return LYNX_ERR_HIP; }            \
+      if (_L->profiling) {                                                     \
+        (void)hipEventRecord(_L->ev_end[slot], (cx).st);                       \
+        _L->ev_recorded[slot] = true;                                          \
+      }                                                                        \
+    }                                                                          \
   } while (0)
+
+// profile slots: 1..13 = forward operators; then the backward kernels in order
+enum BackwardSlot {
+  kB13Dropout = 14, kB12Dgrad, kB12Wgrad, kB11Gelu, kB10Dgrad, kB10Wgrad, kB9LayerNorm,
+  kB8Dropout, kB7Dgrad, kB7Wgrad, kB6DPd, kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Dgrad, kB2Wgrad,
+  kB2BiasGrad, kB1LayerNorm, kNumSlots
+};
+static_assert(kNumSlots <= LYNX_PROFILE_SLOTS, "profile slots");
+const char* const kSlotNames[kNumSlots] = {
+    "", "op1_layernorm1", "op2_qkv_gemm", "op3_scores", "op4_softmax_dropout", "op5_attn_dropout",
+    "op6_context", "op7_attn_proj_gemm", "op8_bias_dropout_add1", "op9_layernorm2", "op10_fc1_gemm",
+    "op11_gelu", "op12_fc2_gemm", "op13_bias_dropout_add2", "b13_dropout_bwd", "b12_fc2_dgrad",
+    "b12_fc2_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad", "b10_fc1_wgrad", "b9_layernorm2_bwd",
+    "b8_dropout_bwd", "b7_proj_dgrad", "b7_proj_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd",
+    "b3_dq", "b3_dk", "b2_qkv_dgrad", "b2_qkv_wgrad", "b2_bias_grad", "b1_layernorm1_bwd"};
 
 char* act_ptr(const Ctx& cx, int i) {
   if (i == 0) return const_cast<char*>(static_cast<const char*>(cx.L->x));
@@ -262,7 +289,7 @@ lynx_status run_op(Ctx& cx, int i, bool fuse_dropout = false, bool write_p = tru
   if (i == 4 && !write_p) {
     // P itself is not wanted: only Pd is produced
     LYNX_TRY(alloc_act(cx, 5));
-    LYNX_LAUNCH(cx, lynx::softmax_dropout_fwd(dt, act_ptr(cx, 3), nullptr, act_ptr(cx, 5),
+    LYNX_LAUNCH(cx, i, lynx::softmax_dropout_fwd(dt, act_ptr(cx, 3), nullptr, act_ptr(cx, 5),
                                               attn_shape(L), 1.0f / sqrtf(static_cast<float>(D.d)),
                                               dropout_params(L), cx.st));
     return LYNX_OK;
@@ -270,16 +297,16 @@ lynx_status run_op(Ctx& cx, int i, bool fuse_dropout = false, bool write_p = tru
   LYNX_TRY(alloc_act(cx, i));
   switch (i) {
     case 1:
-      LYNX_LAUNCH(cx, lynx::layernorm_fwd(dt, act_ptr(cx, 0), w.g1, w.be1, act_ptr(cx, 1),
+      LYNX_LAUNCH(cx, i, lynx::layernorm_fwd(dt, act_ptr(cx, 0), w.g1, w.be1, act_ptr(cx, 1),
                                           stats_ptr(cx, 1), stats_ptr(cx, 1) + D.T, D.T, D.h,
                                           L->cfg.ln_eps, cx.st));
       break;
     case 2:
-      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 1), w.wqkv, w.bqkv, act_ptr(cx, 2), D.T,
+      LYNX_LAUNCH(cx, i, lynx::gemm(dt, linear_fwd(act_ptr(cx, 1), w.wqkv, w.bqkv, act_ptr(cx, 2), D.T,
                                                 3 * D.p, D.h), cx.st));
       break;
     case 3:
-      LYNX_LAUNCH(cx, lynx::gemm(dt, attn_outer(col_block(act_ptr(cx, 2), D, 0), 3 * D.p,
+      LYNX_LAUNCH(cx, i, lynx::gemm(dt, attn_outer(col_block(act_ptr(cx, 2), D, 0), 3 * D.p,
                                                 col_block(act_ptr(cx, 2), D, 1), 3 * D.p,
                                                 act_ptr(cx, 3), D), cx.st));
       break;
@@ -289,47 +316,47 @@ lynx_status run_op(Ctx& cx, int i, bool fuse_dropout = false, bool write_p = tru
         LYNX_TRY(alloc_act(cx, 5));
         pd = act_ptr(cx, 5);
       }
-      LYNX_LAUNCH(cx, lynx::softmax_dropout_fwd(dt, act_ptr(cx, 3), act_ptr(cx, 4), pd,
+      LYNX_LAUNCH(cx, i, lynx::softmax_dropout_fwd(dt, act_ptr(cx, 3), act_ptr(cx, 4), pd,
                                                 attn_shape(L), 1.0f / sqrtf(static_cast<float>(D.d)),
                                                 dropout_params(L), cx.st));
       break;
     }
     case 5:
-      LYNX_LAUNCH(cx, lynx::attn_dropout_fwd(dt, act_ptr(cx, 4), act_ptr(cx, 5), attn_shape(L),
+      LYNX_LAUNCH(cx, i, lynx::attn_dropout_fwd(dt, act_ptr(cx, 4), act_ptr(cx, 5), attn_shape(L),
                                              dropout_params(L), cx.st));
       break;
     case 6:
-      LYNX_LAUNCH(cx, lynx::gemm(dt, attn_rows(act_ptr(cx, 5), col_block(act_ptr(cx, 2), D, 2),
+      LYNX_LAUNCH(cx, i, lynx::gemm(dt, attn_rows(act_ptr(cx, 5), col_block(act_ptr(cx, 2), D, 2),
                                                3 * D.p, act_ptr(cx, 6), D.p, D), cx.st));
       break;
     case 7:
-      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 6), w.wo, nullptr, act_ptr(cx, 7), D.T,
+      LYNX_LAUNCH(cx, i, lynx::gemm(dt, linear_fwd(act_ptr(cx, 6), w.wo, nullptr, act_ptr(cx, 7), D.T,
                                                 D.h, D.p), cx.st));
       break;
     case 8:
-      LYNX_LAUNCH(cx, lynx::bias_dropout_add_fwd(dt, act_ptr(cx, 7), w.bo, act_ptr(cx, 0),
+      LYNX_LAUNCH(cx, i, lynx::bias_dropout_add_fwd(dt, act_ptr(cx, 7), w.bo, act_ptr(cx, 0),
                                                  act_ptr(cx, 8), D.T, D.h, 1, dropout_params(L),
                                                  cx.st));
       break;
     case 9:
-      LYNX_LAUNCH(cx, lynx::layernorm_fwd(dt, act_ptr(cx, 8), w.g2, w.be2, act_ptr(cx, 9),
+      LYNX_LAUNCH(cx, i, lynx::layernorm_fwd(dt, act_ptr(cx, 8), w.g2, w.be2, act_ptr(cx, 9),
                                           stats_ptr(cx, 9), stats_ptr(cx, 9) + D.T, D.T, D.h,
                                           L->cfg.ln_eps, cx.st));
       break;
     case 10:
-      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 9), w.w1, w.b1, act_ptr(cx, 10), D.T,
+      LYNX_LAUNCH(cx, i, lynx::gemm(dt, linear_fwd(act_ptr(cx, 9), w.w1, w.b1, act_ptr(cx, 10), D.T,
                                                 D.f, D.h), cx.st));
       break;
     case 11:
-      LYNX_LAUNCH(cx, lynx::gelu_fwd(dt, act_ptr(cx, 10), act_ptr(cx, 11),
+      LYNX_LAUNCH(cx, i, lynx::gelu_fwd(dt, act_ptr(cx, 10), act_ptr(cx, 11),
                                      static_cast<size_t>(D.T) * D.f, cx.st));
       break;
     case 12:
-      LYNX_LAUNCH(cx, lynx::gemm(dt, linear_fwd(act_ptr(cx, 11), w.w2, nullptr, act_ptr(cx, 12),
+      LYNX_LAUNCH(cx, i, lynx::gemm(dt, linear_fwd(act_ptr(cx, 11), w.w2, nullptr, act_ptr(cx, 12),
                                                 D.T, D.h, D.f), cx.st));
       break;
     case 13:
-      LYNX_LAUNCH(cx, lynx::bias_dropout_add_fwd(dt, act_ptr(cx, 12), w.b2, act_ptr(cx, 8),
+      LYNX_LAUNCH(cx, i, lynx::bias_dropout_add_fwd(dt, act_ptr(cx, 12), w.b2, act_ptr(cx, 8),
                                                  act_ptr(cx, 13), D.T, D.h, 2, dropout_params(L),
                                                  cx.st));
       break;
@@ -436,32 +463,32 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
 
   // B13: OUT = X2 + keep2 (V2 + b2) c
   LYNX_TRY(alloc_temp(cx, th, &t_dv2));
-  LYNX_LAUNCH(cx, lynx::dropout_bwd(dt, d_out, temp_ptr(cx, t_dv2), gr->b2, scr, D.T, D.h, 2,
+  LYNX_LAUNCH(cx, kB13Dropout, lynx::dropout_bwd(dt, d_out, temp_ptr(cx, t_dv2), gr->b2, scr, D.T, D.h, 2,
                                     dropout_params(L), cx.st));
   // B12: V2 = G W2^T
   LYNX_TRY(alloc_temp(cx, tf, &t_dg));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T,
+  LYNX_LAUNCH(cx, kB12Dgrad, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T,
                                               D.h, D.f), cx.st));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T,
+  LYNX_LAUNCH(cx, kB12Wgrad, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T,
                                               D.h, D.f), cx.st));
   free_temp(cx, &t_dv2);
   free_act(cx, 11);
   // B11: G = gelu(U)
   LYNX_TRY(alloc_temp(cx, tf, &t_du));
-  LYNX_LAUNCH(cx, lynx::gelu_bwd(dt, temp_ptr(cx, t_dg), act_ptr(cx, 10), temp_ptr(cx, t_du),
+  LYNX_LAUNCH(cx, kB11Gelu, lynx::gelu_bwd(dt, temp_ptr(cx, t_dg), act_ptr(cx, 10), temp_ptr(cx, t_du),
                                  gr->b1, scr, D.T, D.f, cx.st));
   free_temp(cx, &t_dg);
   free_act(cx, 10);
   // B10: U = Y2 W1^T + b1
   LYNX_TRY(alloc_temp(cx, th, &t_dy2));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T,
+  LYNX_LAUNCH(cx, kB10Dgrad, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T,
                                               D.f, D.h), cx.st));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f,
+  LYNX_LAUNCH(cx, kB10Wgrad, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f,
                                               D.h), cx.st));
   free_temp(cx, &t_du);
   // B9: Y2 = LN2(X2); dX2 = dOUT + dLN
   LYNX_TRY(alloc_temp(cx, th, &t_dx2));
-  LYNX_LAUNCH(cx, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy2), act_ptr(cx, 8), stats_ptr(cx, 9),
+  LYNX_LAUNCH(cx, kB9LayerNorm, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy2), act_ptr(cx, 8), stats_ptr(cx, 9),
                                       stats_ptr(cx, 9) + D.T, w.g2, d_out, temp_ptr(cx, t_dx2),
                                       gr->g2, gr->be2, scr, D.T, D.h, cx.st));
   free_temp(cx, &t_dy2);
@@ -469,13 +496,13 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   free_act(cx, 8);
   // B8: X2 = X + keep1 (O + bo) c
   LYNX_TRY(alloc_temp(cx, th, &t_do));
-  LYNX_LAUNCH(cx, lynx::dropout_bwd(dt, temp_ptr(cx, t_dx2), temp_ptr(cx, t_do), gr->bo, scr, D.T,
+  LYNX_LAUNCH(cx, kB8Dropout, lynx::dropout_bwd(dt, temp_ptr(cx, t_dx2), temp_ptr(cx, t_do), gr->bo, scr, D.T,
                                     D.h, 1, dropout_params(L), cx.st));
   // B7: O = C Wo^T
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * D.p * e, &t_dc));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T,
+  LYNX_LAUNCH(cx, kB7Dgrad, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T,
                                               D.h, D.p), cx.st));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h,
+  LYNX_LAUNCH(cx, kB7Wgrad, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h,
                                               D.p), cx.st));
   free_temp(cx, &t_do);
   free_act(cx, 6);
@@ -484,39 +511,39 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * 3 * D.p * e, &t_dqkv));
   char* dqkv = temp_ptr(cx, t_dqkv);
   const char* qkv = act_ptr(cx, 2);
-  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_outer(temp_ptr(cx, t_dc), D.p, col_block(qkv, D, 2), 3 * D.p,
+  LYNX_LAUNCH(cx, kB6DPd, lynx::gemm(dt, attn_outer(temp_ptr(cx, t_dc), D.p, col_block(qkv, D, 2), 3 * D.p,
                                             temp_ptr(cx, t_dpd), D), cx.st));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_cols(act_ptr(cx, 5), temp_ptr(cx, t_dc), D.p,
+  LYNX_LAUNCH(cx, kB6DV, lynx::gemm(dt, attn_cols(act_ptr(cx, 5), temp_ptr(cx, t_dc), D.p,
                                            const_cast<char*>(col_block(dqkv, D, 2)), 3 * D.p, D),
                              cx.st));
   free_temp(cx, &t_dc);
   free_act(cx, 5);
   // B5 + B4: Pd = keep0 P c, P = softmax(S / sqrt(d)); dS overwrites dPd
-  LYNX_LAUNCH(cx, lynx::softmax_dropout_bwd(dt, temp_ptr(cx, t_dpd), act_ptr(cx, 4),
+  LYNX_LAUNCH(cx, kB54Softmax, lynx::softmax_dropout_bwd(dt, temp_ptr(cx, t_dpd), act_ptr(cx, 4),
                                             temp_ptr(cx, t_dpd), attn_shape(L),
                                             1.0f / sqrtf(static_cast<float>(D.d)), dropout_params(L),
                                             cx.st));
   free_act(cx, 4);
   // B3: S = Q K^T
-  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_rows(temp_ptr(cx, t_dpd), col_block(qkv, D, 1), 3 * D.p,
+  LYNX_LAUNCH(cx, kB3DQ, lynx::gemm(dt, attn_rows(temp_ptr(cx, t_dpd), col_block(qkv, D, 1), 3 * D.p,
                                            const_cast<char*>(col_block(dqkv, D, 0)), 3 * D.p, D),
                              cx.st));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, attn_cols(temp_ptr(cx, t_dpd), col_block(qkv, D, 0), 3 * D.p,
+  LYNX_LAUNCH(cx, kB3DK, lynx::gemm(dt, attn_cols(temp_ptr(cx, t_dpd), col_block(qkv, D, 0), 3 * D.p,
                                            const_cast<char*>(col_block(dqkv, D, 1)), 3 * D.p, D),
                              cx.st));
   free_temp(cx, &t_dpd);
   free_act(cx, 3);
   // B2: QKV = Y1 Wqkv^T + bqkv
   LYNX_TRY(alloc_temp(cx, th, &t_dy1));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
+  LYNX_LAUNCH(cx, kB2Dgrad, lynx::gemm(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
                              cx.st));
-  LYNX_LAUNCH(cx, lynx::gemm(dt, linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h),
+  LYNX_LAUNCH(cx, kB2Wgrad, lynx::gemm(dt, linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h),
                              cx.st));
-  LYNX_LAUNCH(cx, lynx::column_sum(dt, dqkv, gr->bqkv, scr, D.T, 3 * D.p, cx.st));
+  LYNX_LAUNCH(cx, kB2BiasGrad, lynx::column_sum(dt, dqkv, gr->bqkv, scr, D.T, 3 * D.p, cx.st));
   free_temp(cx, &t_dqkv);
   free_act(cx, 2);
   // B1: Y1 = LN1(X); dX = dX2 + dLN
-  LYNX_LAUNCH(cx, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy1), act_ptr(cx, 0), stats_ptr(cx, 1),
+  LYNX_LAUNCH(cx, kB1LayerNorm, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy1), act_ptr(cx, 0), stats_ptr(cx, 1),
                                       stats_ptr(cx, 1) + D.T, w.g1, temp_ptr(cx, t_dx2), d_x, gr->g1,
                                       gr->be1, scr, D.T, D.h, cx.st));
   free_temp(cx, &t_dy1);
@@ -577,6 +604,7 @@ lynx_status lynx_layer_create(const lynx_layer_config* cfg, void* workspace, siz
 
 lynx_status lynx_layer_destroy(lynx_layer_t layer) {
   if (layer == nullptr) return LYNX_ERR_INVALID_ARG;
+  (void)lynx_layer_set_profiling(layer, 0);
   delete layer;
   return LYNX_OK;
 }
@@ -702,6 +730,45 @@ lynx_status lynx_dropout_mask(const lynx_layer_config* cfg, uint64_t step, int s
   else
     e = lynx::dropout_mask_hidden(out, static_cast<size_t>(D.T) * D.h, site, dp, st);
   return e == hipSuccess ? LYNX_OK : LYNX_ERR_HIP;
+}
+
+lynx_status lynx_layer_set_profiling(lynx_layer_t L, int on) {
+  if (L == nullptr) return LYNX_ERR_INVALID_ARG;
+  if ((on != 0) == L->profiling) return LYNX_OK;
+  if (on) {
+    for (int i = 0; i < LYNX_PROFILE_SLOTS; ++i) {
+      if (hipEventCreate(&L->ev_begin[i]) != hipSuccess || hipEventCreate(&L->ev_end[i]) != hipSuccess)
+        return LYNX_ERR_HIP;
+      L->ev_recorded[i] = false;
+    }
+    L->profiling = true;
+  } else {
+    L->profiling = false;
+    for (int i = 0; i < LYNX_PROFILE_SLOTS; ++i) {
+      (void)hipEventDestroy(L->ev_begin[i]);
+      (void)hipEventDestroy(L->ev_end[i]);
+      L->ev_recorded[i] = false;
+    }
+  }
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_profile_ms(lynx_layer_t L, float* ms_out) {
+  if (L == nullptr || ms_out == nullptr) return LYNX_ERR_INVALID_ARG;
+  if (!L->profiling) return LYNX_ERR_STATE;
+  for (int i = 0; i < LYNX_PROFILE_SLOTS; ++i) {
+    ms_out[i] = -1.0f;
+    if (!L->ev_recorded[i]) continue;
+    if (hipEventSynchronize(L->ev_end[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms_out[i], L->ev_begin[i], L->ev_end[i]) != hipSuccess)
+      return LYNX_ERR_HIP;
+    L->ev_recorded[i] = false;
+  }
+  return LYNX_OK;
+}
+
+const char* lynx_profile_slot_name(int slot) {
+  return (slot >= 1 && slot < kNumSlots) ? kSlotNames[slot] : "";
 }
 
 const char* lynx_status_string(lynx_status s) {
