@@ -3,19 +3,26 @@
 //   C[M, N] = sum_k A(m, k) * B(k, n) (+ bias[n]),   fp32 accumulation
 //
 // Either operand may be stored "K-major" (the contraction index is the
-// contiguous one: activations and weights in a forward linear layer) or
+// contiguous one: activations and weights of a forward linear layer) or
 // "MN-major" (the contraction index is the row index: the weight in an input
-// gradient, both operands in a weight gradient).  One workgroup of 8
-// wavefronts owns a BM x BN output tile and walks K in slabs of 64:
-//   global -> registers (16-byte loads) -> LDS, double buffered;
-//   K-major slabs sit in LDS as [mn][64] with the 16-byte chunk index XORed
-//   with (row & 7), so the 32 rows a fragment read touches spread over all
-//   banks; MN-major slabs sit as [64][mn + 16] and are read with the
-//   transposing LDS read (ds_read_b64_tr_b16), which hands each lane four
-//   consecutive k for its own mn - no shuffles and no transposed copies.
+// gradient, both operands in a weight gradient).
+//
+// Design.  One workgroup of 4 wavefronts (one per SIMD, up to 512 registers
+// each) owns a BM x BN output tile (256 x 256 when it divides); each
+// wavefront owns a quarter of it, so every fragment read from LDS feeds four
+// MFMAs.  K is walked in slabs of 32.  Slabs travel global memory -> LDS
+// directly (global_load_lds_dwordx4, no staging registers) through a ring of
+// four LDS stages: while one slab is multiplied, three more are in flight,
+// which is what it takes to cover L2 latency at this MFMA rate.  Bank
+// conflicts are avoided by permuting 16-byte chunks, applied on the global
+// address side since a direct load writes lane i to LDS offset 16 i:
+//   K-major slab  [mn][32]: chunk ^= (row >> 1) & 3
+//   MN-major slab [32][mn]: chunk ^= (k & 3) << 1, read with the transposing
+//     LDS read (ds_read_b64_tr_b16) that hands each lane four consecutive k.
 // The product is formed transposed (B fragment as the first MFMA operand) so
-// that every lane ends up with four consecutive n of one row m and can store
-// 8 bytes at a time.
+// each lane ends with four consecutive n of one row m and stores 8 bytes.
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -24,11 +31,13 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short short8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kBK = 64;          // K slab
-constexpr int kThreads = 512;    // 8 wavefronts
-constexpr int kPadMN = 16;       // row padding (elements) of MN-major slabs
+constexpr int kBK = 32;        // K slab
+constexpr int kStages = 4;     // LDS ring depth
+constexpr int kThreads = 256;  // 4 wavefronts
+constexpr int kWaves = kThreads / kWave;
 
 struct MfmaGemmArgs {
   const bf16_t* A; long long lda;
@@ -39,71 +48,91 @@ struct MfmaGemmArgs {
   int tiles_m, tiles_n;
 };
 
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
+// vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+// Workgroup barrier that neither the optimiser nor the scheduler moves memory
+// accesses across (and that, unlike __syncthreads, does not drain the loads
+// still in flight).
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ void wait_lgkmcnt0() {
+  __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8));
+}
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+// One slab (ROWS x 32 elements) of an operand.
 template <int ROWS, bool KMAJOR>
-struct Slab {  // LDS footprint of one operand slab, in bf16 elements
-  static constexpr int kElems = KMAJOR ? ROWS * kBK : kBK * (ROWS + kPadMN);
-  static constexpr int kChunks = ROWS * kBK / 8;            // 16-byte chunks
-  static constexpr int kPerThread = kChunks / kThreads;
-  static_assert(kChunks % kThreads == 0, "slab must divide over the workgroup");
+struct Slab {
+  static constexpr int kElems = ROWS * kBK;
+  static constexpr int kLoadsPerWave = ROWS / 16 / kWaves;  // 1 KB direct loads per wavefront
+  static_assert(ROWS % (16 * kWaves) == 0, "slab must split over the wavefronts");
+
+  // Global element offset, relative to the slab origin (row0, k0), that lane
+  // `lane` fetches in this wavefront's j-th load; and that load's LDS offset.
+  __device__ static __forceinline__ long long global_offset(int wave, int j, int lane, long long ld) {
+    const int q = wave + kWaves * j;  // which 1 KB piece of the slab
+    if (KMAJOR) {
+      const int row = 16 * q + (lane >> 2);
+      const int chunk = (lane & 3) ^ ((row >> 1) & 3);
+      return static_cast<long long>(row) * ld + chunk * 8;
+    } else {
+      constexpr int kRowChunks = ROWS / 8;          // 16-byte chunks per k-row
+      constexpr int kRowsPerLoad = 64 / kRowChunks; // k-rows per 1 KB
+      const int k = kRowsPerLoad * q + lane / kRowChunks;
+      const int chunk = (lane % kRowChunks) ^ ((k & 3) << 1);
+      return static_cast<long long>(k) * ld + chunk * 8;
+    }
+  }
+  __device__ static __forceinline__ int lds_offset(int wave, int j) { return (wave + kWaves * j) * 512; }
+
+  // MFMA operand fragment: 8 consecutive k (at 16 ks + 8 (lane / 32)) of slab
+  // row tile_row0 + lane % 32.
+  __device__ static __forceinline__ bf16x8_t fragment(const bf16_t* slab, int tile_row0, int ks, int lane) {
+    if (KMAJOR) {
+      const int r = tile_row0 + (lane & 31);
+      const int chunk = (2 * ks + (lane >> 5)) ^ ((r >> 1) & 3);
+      return *reinterpret_cast<const bf16x8_t*>(slab + r * kBK + chunk * 8);
+    } else {
+      // four blocks of 16 lanes: block b holds rows (b & 1) * 16.. of k-group b >> 1; in a
+      // block, lane i points at k-row i / 4, columns 4 (i % 4)..+3 and receives column i.
+      const int b = lane >> 4, i = lane & 15;
+      const int k = ks * 16 + (b >> 1) * 8 + (i >> 2);
+      const int col = tile_row0 + (b & 1) * 16 + ((i & 3) << 2);
+      const int sw = (k & 3) << 1;  // same for k and k + 4
+      const bf16_t* p = slab + k * ROWS + (((col >> 3) ^ sw) << 3) + (col & 7);
+      typedef __attribute__((address_space(3))) short4_t* lds_ptr_t;
+      const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+      const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * ROWS));
+      const short8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8_t, v);
+    }
+  }
 };
 
-// Global address (in elements) of 16-byte chunk c of the slab starting at
-// (row0, k0), and the LDS element offset it is staged to.
-template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ void chunk_coords(int c, long long ld, int row0, int k0, long long* goff,
-                                             int* loff) {
-  if (KMAJOR) {
-    const int r = c >> 3, kc = c & 7;                      // 8 chunks per row of 64 k
-    *goff = static_cast<long long>(row0 + r) * ld + k0 + kc * 8;
-    *loff = r * kBK + ((kc ^ (r & 7)) << 3);
-  } else {
-    constexpr int kRowChunks = ROWS / 8;
-    const int kr = c / kRowChunks, mc = c - kr * kRowChunks;
-    *goff = static_cast<long long>(k0 + kr) * ld + row0 + mc * 8;
-    *loff = kr * (ROWS + kPadMN) + mc * 8;
-  }
-}
-
-// One MFMA operand fragment: 8 consecutive k (at 16*ks + 8*(lane/32)) of row
-// `r` (= tile base + lane%32) of the slab.
-template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ bf16x8_t read_fragment(const bf16_t* slab, int tile_row0, int ks, int lane) {
-  if (KMAJOR) {
-    const int r = tile_row0 + (lane & 31);
-    const int chunk = (ks * 2 + (lane >> 5)) ^ (r & 7);
-    return *reinterpret_cast<const bf16x8_t*>(slab + r * kBK + (chunk << 3));
-  } else {
-    // lanes form four blocks of 16: block b covers rows (b&1)*16.. and k-group b>>1;
-    // inside a block lane i points at k-row i/4, columns 4*(i%4)..+3, and receives
-    // the four k of column i.
-    const int b = lane >> 4, i = lane & 15;
-    const int k = ks * 16 + (b >> 1) * 8 + (i >> 2);
-    const int col = tile_row0 + (b & 1) * 16 + ((i & 3) << 2);
-    const bf16_t* p = slab + k * (ROWS + kPadMN) + col;
-    typedef __attribute__((address_space(3))) short4_t* lds_ptr_t;
-    const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
-    const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * (ROWS + kPadMN)));
-    typedef short short8_t __attribute__((ext_vector_type(8)));
-    const short8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    return __builtin_bit_cast(bf16x8_t, v);
-  }
-}
-
-template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WAVES_M, int WAVES_N>
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN>
 __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
-  static_assert(WAVES_M * WAVES_N == kThreads / kWave, "8 wavefronts");
-  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int WM = BM / 2, WN = BN / 2;  // wavefronts in a 2 x 2 grid
   constexpr int TM = WM / 32, TN = WN / 32;
-  using SlabA = Slab<BM, A_KMAJOR>;
-  using SlabB = Slab<BN, B_KMAJOR>;
-  constexpr int kStage = SlabA::kElems + SlabB::kElems;
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+  using SA = Slab<BM, A_KMAJOR>;
+  using SB = Slab<BN, B_KMAJOR>;
+  constexpr int kStageElems = SA::kElems + SB::kElems;
+  constexpr int kLoads = SA::kLoadsPerWave + SB::kLoadsPerWave;  // per wavefront per slab
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
   // workgroup -> output tile.  Consecutive workgroup ids land on different
   // XCDs (round robin over 8), so give each XCD a contiguous run of tiles,
-  // and order tiles in bands of 8 tile-rows so a band's A and B panels stay
-  // in that XCD's L2.
+  // ordered in bands of 8 tile-rows so a band's panels stay in that XCD's L2.
   const int ntiles = g.tiles_m * g.tiles_n;
   int tile = blockIdx.x;
   {
@@ -118,8 +147,36 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   const int tn = in_band / band_rows;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+
+  // this lane's global source of each direct load, at slab 0
+  const bf16_t* ga[SA::kLoadsPerWave];
+  const bf16_t* gb[SB::kLoadsPerWave];
+#pragma unroll
+  for (int j = 0; j < SA::kLoadsPerWave; ++j)
+    ga[j] = g.A + (A_KMAJOR ? static_cast<long long>(m0) * g.lda : static_cast<long long>(m0)) +
+            SA::global_offset(wave, j, lane, g.lda);
+#pragma unroll
+  for (int j = 0; j < SB::kLoadsPerWave; ++j)
+    gb[j] = g.B + (B_KMAJOR ? static_cast<long long>(n0) * g.ldb : static_cast<long long>(n0)) +
+            SB::global_offset(wave, j, lane, g.ldb);
+  const long long a_step = A_KMAJOR ? kBK : kBK * g.lda;  // elements per slab
+  const long long b_step = B_KMAJOR ? kBK : kBK * g.ldb;
+
+  auto issue_slab = [&](int kt) {  // slab kt -> ring stage kt % kStages
+    bf16_t* sa = smem + (kt & (kStages - 1)) * kStageElems;
+    bf16_t* sb = sa + SA::kElems;
+#pragma unroll
+    for (int j = 0; j < SA::kLoadsPerWave; ++j)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(ga[j] + kt * a_step),
+                                       (lds_void_ptr)(sa + SA::lds_offset(wave, j)), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < SB::kLoadsPerWave; ++j)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(gb[j] + kt * b_step),
+                                       (lds_void_ptr)(sb + SB::lds_offset(wave, j)), 16, 0, 0);
+  };
 
   floatx16_t acc[TN][TM];
 #pragma unroll
@@ -129,63 +186,74 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 stage_a[SlabA::kPerThread], stage_b[SlabB::kPerThread];
-  auto load_slabs = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < SlabA::kPerThread; ++i) {
-      long long go; int lo;
-      chunk_coords<BM, A_KMAJOR>(tid + i * kThreads, g.lda, m0, k0, &go, &lo);
-      stage_a[i] = *reinterpret_cast<const uint4*>(g.A + go);
-    }
-#pragma unroll
-    for (int i = 0; i < SlabB::kPerThread; ++i) {
-      long long go; int lo;
-      chunk_coords<BN, B_KMAJOR>(tid + i * kThreads, g.ldb, n0, k0, &go, &lo);
-      stage_b[i] = *reinterpret_cast<const uint4*>(g.B + go);
-    }
-  };
-  auto store_slabs = [&](int buf) {
-    bf16_t* sa = smem + buf * kStage;
-    bf16_t* sb = sa + SlabA::kElems;
-#pragma unroll
-    for (int i = 0; i < SlabA::kPerThread; ++i) {
-      long long go; int lo;
-      chunk_coords<BM, A_KMAJOR>(tid + i * kThreads, g.lda, m0, 0, &go, &lo);
-      *reinterpret_cast<uint4*>(sa + lo) = stage_a[i];
-    }
-#pragma unroll
-    for (int i = 0; i < SlabB::kPerThread; ++i) {
-      long long go; int lo;
-      chunk_coords<BN, B_KMAJOR>(tid + i * kThreads, g.ldb, n0, 0, &go, &lo);
-      *reinterpret_cast<uint4*>(sb + lo) = stage_b[i];
-    }
-  };
-
   const int nk = g.K / kBK;
-  load_slabs(0);
-  store_slabs(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_slabs((kt + 1) * kBK);
-    const bf16_t* sa = smem + buf * kStage;
-    const bf16_t* sb = sa + SlabA::kElems;
+  // prologue: three slabs in flight, the first one landed
+  issue_slab(0);
+  if (nk > 1) issue_slab(1);
+  if (nk > 2) issue_slab(2);
+  if (nk > 2) wait_vmcnt<2 * kLoads>();
+  else if (nk > 1) wait_vmcnt<kLoads>();
+  else wait_vmcnt<0>();
+  block_barrier();
+
+  bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  {
+    const bf16_t* sa = smem;
+    const bf16_t* sb = sa + SA::kElems;
 #pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      bf16x8_t fa[TM], fb[TN];
+    for (int j = 0; j < TM; ++j) fa0[j] = SA::fragment(sa, wm0 + 32 * j, 0, lane);
 #pragma unroll
-      for (int j = 0; j < TM; ++j) fa[j] = read_fragment<BM, A_KMAJOR>(sa, wm0 + j * 32, ks, lane);
-#pragma unroll
-      for (int i = 0; i < TN; ++i) fb[i] = read_fragment<BN, B_KMAJOR>(sb, wn0 + i * 32, ks, lane);
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) store_slabs(buf ^ 1);
-    __syncthreads();
+    for (int i = 0; i < TN; ++i) fb0[i] = SB::fragment(sb, wn0 + 32 * i, 0, lane);
   }
+
+  // One slab: [refill ring] [read 2nd-half fragments] [MFMA 1st half] [next slab landed?]
+  // [barrier] [read next slab's 1st-half fragments] [MFMA 2nd half].  `steady` = three
+  // more slabs exist, so the refill and the waits need no conditions.
+  auto slab_step = [&](int kt, auto steady_tag) {
+    constexpr bool steady = decltype(steady_tag)::value;
+    const bf16_t* sa = smem + (kt & (kStages - 1)) * kStageElems;
+    const bf16_t* sb = sa + SA::kElems;
+    // refill the stage every wavefront finished reading before the last barrier
+    if (steady || kt + 3 < nk) issue_slab(kt + 3);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) fa1[j] = SA::fragment(sa, wm0 + 32 * j, 1, lane);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) fb1[i] = SB::fragment(sb, wn0 + 32 * i, 1, lane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // the next slab must have landed (two newer ones may still be in flight), and all
+    // of this wavefront's reads of the current slab must be complete
+    if (steady || kt + 3 < nk) wait_vmcnt<2 * kLoads>();
+    else if (kt + 2 < nk) wait_vmcnt<kLoads>();
+    else wait_vmcnt<0>();
+    wait_lgkmcnt0();
+    block_barrier();
+    if (steady || kt + 1 < nk) {
+      const bf16_t* na = smem + ((kt + 1) & (kStages - 1)) * kStageElems;
+      const bf16_t* nb = na + SA::kElems;
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fa0[j] = SA::fragment(na, wm0 + 32 * j, 0, lane);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fb0[i] = SB::fragment(nb, wn0 + 32 * i, 0, lane);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_lgkmcnt0();  // long since complete; tells the compiler nothing is pending at the loop top
+  };
+  wait_lgkmcnt0();
+  int kt = 0;
+  for (; kt + 3 < nk; ++kt) slab_step(kt, std::true_type{});
+  for (; kt < nk; ++kt) slab_step(kt, std::false_type{});
 
   // acc[i][j][r]: n = wn0 + 32 i + 8 (r/4) + 4 (lane/32) + r%4,  m = wm0 + 32 j + lane%32
 #pragma unroll
@@ -209,12 +277,10 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
     }
 }
 
-template <bool AK, bool BK_, int BM, int BN, int WM_, int WN_>
+template <bool AK, bool BK_, int BM, int BN>
 hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
-  using SA = Slab<BM, AK>;
-  using SB = Slab<BN, BK_>;
-  constexpr size_t smem = 2 * (SA::kElems + SB::kElems) * sizeof(bf16_t);
-  auto kern = gemm_mfma_kernel<AK, BK_, BM, BN, WM_, WN_>;
+  constexpr size_t smem = static_cast<size_t>(kStages) * (BM + BN) * kBK * sizeof(bf16_t);
+  auto kern = gemm_mfma_kernel<AK, BK_, BM, BN>;
   static bool configured = false;  // raise the dynamic LDS limit once per instantiation
   if (!configured) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -233,7 +299,7 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
 template <bool AK, bool BK_>
 hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
   struct Cand { int bm, bn; float weight; };
-  static const Cand cands[4] = {{256, 256, 1.0f}, {256, 128, 0.88f}, {128, 256, 0.88f}, {128, 128, 0.72f}};
+  static const Cand cands[4] = {{256, 256, 1.0f}, {256, 128, 0.8f}, {128, 256, 0.8f}, {128, 128, 0.6f}};
   int best = -1;
   float best_score = 0.f;
   for (int c = 0; c < 4; ++c) {
@@ -247,10 +313,10 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
   a.tiles_m = a.M / cands[best].bm;
   a.tiles_n = a.N / cands[best].bn;
   switch (best) {
-    case 0: return launch<AK, BK_, 256, 256, 2, 4>(a, st);
-    case 1: return launch<AK, BK_, 256, 128, 4, 2>(a, st);
-    case 2: return launch<AK, BK_, 128, 256, 2, 4>(a, st);
-    default: return launch<AK, BK_, 128, 128, 2, 4>(a, st);
+    case 0: return launch<AK, BK_, 256, 256>(a, st);
+    case 1: return launch<AK, BK_, 256, 128>(a, st);
+    case 2: return launch<AK, BK_, 128, 256>(a, st);
+    default: return launch<AK, BK_, 128, 128>(a, st);
   }
 }
 
