@@ -46,6 +46,10 @@ struct MfmaGemmArgs {
   const bf16_t* bias;
   int M, N, K;
   int tiles_m, tiles_n;
+  // batched use (attention): matrix z = z1 * nz2 + z2 starts at these element offsets
+  long long a_z1, a_z2, b_z1, b_z2, c_z1, c_z2;
+  int nz, nz2;
+  int causal;  // CausalMode
 };
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -130,22 +134,39 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
-  // workgroup -> output tile.  Consecutive workgroup ids land on different
-  // XCDs (round robin over 8), so give each XCD a contiguous run of tiles,
-  // ordered in bands of 8 tile-rows so a band's panels stay in that XCD's L2.
-  const int ntiles = g.tiles_m * g.tiles_n;
-  int tile = blockIdx.x;
-  {
+  // workgroup -> output tile
+  int tm, tn;
+  if (g.causal == kCausalOutLower) {
+    // square output, only tiles on or below the diagonal: t = tm (tm + 1) / 2 + tn
+    const int t = blockIdx.x;
+    tm = static_cast<int>((sqrtf(8.0f * static_cast<float>(t) + 1.0f) - 1.0f) * 0.5f);
+    while (tm * (tm + 1) / 2 > t) --tm;
+    while ((tm + 1) * (tm + 2) / 2 <= t) ++tm;
+    tn = t - tm * (tm + 1) / 2;
+  } else {
+    // Consecutive workgroup ids land on different XCDs (round robin over 8), so give
+    // each XCD a contiguous run of tiles, ordered in bands of 8 tile-rows so a band's
+    // panels stay in that XCD's L2.
+    const int ntiles = g.tiles_m * g.tiles_n;
+    int tile = blockIdx.x;
     const int per_xcd = ntiles / 8;
     if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
+    constexpr int kBand = 8;
+    const int band = tile / (kBand * g.tiles_n);
+    const int band_rows = min(kBand, g.tiles_m - band * kBand);
+    const int in_band = tile - band * kBand * g.tiles_n;
+    tm = band * kBand + in_band % band_rows;
+    tn = in_band / band_rows;
   }
-  constexpr int kBand = 8;
-  const int band = tile / (kBand * g.tiles_n);
-  const int band_rows = min(kBand, g.tiles_m - band * kBand);
-  const int in_band = tile - band * kBand * g.tiles_n;
-  const int tm = band * kBand + in_band % band_rows;
-  const int tn = in_band / band_rows;
   const int m0 = tm * BM, n0 = tn * BN;
+  // contraction range: causal products skip the slabs that are identically zero
+  int k_begin = 0, k_end = g.K;
+  if (g.causal == kCausalKLeM) k_end = min(g.K, m0 + BM);
+  if (g.causal == kCausalKGeM) k_begin = m0;
+  const int z1 = blockIdx.y / g.nz2, z2 = blockIdx.y - z1 * g.nz2;
+  const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2;
+  const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
+  bf16_t* Cbase = g.C + z1 * g.c_z1 + z2 * g.c_z2;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -156,11 +177,13 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   const bf16_t* gb[SB::kLoadsPerWave];
 #pragma unroll
   for (int j = 0; j < SA::kLoadsPerWave; ++j)
-    ga[j] = g.A + (A_KMAJOR ? static_cast<long long>(m0) * g.lda : static_cast<long long>(m0)) +
+    ga[j] = Abase + (A_KMAJOR ? static_cast<long long>(m0) * g.lda + k_begin
+                              : static_cast<long long>(k_begin) * g.lda + m0) +
             SA::global_offset(wave, j, lane, g.lda);
 #pragma unroll
   for (int j = 0; j < SB::kLoadsPerWave; ++j)
-    gb[j] = g.B + (B_KMAJOR ? static_cast<long long>(n0) * g.ldb : static_cast<long long>(n0)) +
+    gb[j] = Bbase + (B_KMAJOR ? static_cast<long long>(n0) * g.ldb + k_begin
+                              : static_cast<long long>(k_begin) * g.ldb + n0) +
             SB::global_offset(wave, j, lane, g.ldb);
   const long long a_step = A_KMAJOR ? kBK : kBK * g.lda;  // elements per slab
   const long long b_step = B_KMAJOR ? kBK : kBK * g.ldb;
@@ -186,7 +209,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = g.K / kBK;
+  const int nk = (k_end - k_begin) / kBK;
   // prologue: three slabs in flight, the first one landed
   issue_slab(0);
   if (nk > 1) issue_slab(1);
@@ -272,7 +295,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
         uint2 o;
         o.x = pack_bf16(acc[i][j][4 * q + 0] + bv[0], acc[i][j][4 * q + 1] + bv[1]);
         o.y = pack_bf16(acc[i][j][4 * q + 2] + bv[2], acc[i][j][4 * q + 3] + bv[3]);
-        *reinterpret_cast<uint2*>(g.C + static_cast<long long>(m) * g.ldc + n) = o;
+        *reinterpret_cast<uint2*>(Cbase + static_cast<long long>(m) * g.ldc + n) = o;
       }
     }
 }
@@ -289,7 +312,8 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n), dim3(kThreads), smem, st, a);
+  const int ntiles = a.causal == kCausalOutLower ? a.tiles_m * (a.tiles_m + 1) / 2 : a.tiles_m * a.tiles_n;
+  hipLaunchKernelGGL(kern, dim3(ntiles, a.nz), dim3(kThreads), smem, st, a);
   return hipGetLastError();
 }
 
@@ -298,6 +322,18 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
 // round of workgroups).
 template <bool AK, bool BK_>
 hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
+  if (a.causal != kCausalNone) {
+    // attention products: memory-bound, and the zero padding of the seq x seq operands
+    // reaches the next multiple of 128 only, so contraction-restricted products use
+    // 128-row tiles; the score-shaped ones take the largest square tile
+    if (a.causal == kCausalOutLower && a.M % 256 == 0) {
+      a.tiles_m = a.tiles_n = a.M / 256;
+      return launch<AK, BK_, 256, 256>(a, st);
+    }
+    a.tiles_m = a.M / 128;
+    a.tiles_n = a.N / 128;
+    return launch<AK, BK_, 128, 128>(a, st);
+  }
   struct Cand { int bm, bn; float weight; };
   static const Cand cands[4] = {{256, 256, 1.0f}, {256, 128, 0.8f}, {128, 256, 0.8f}, {128, 128, 0.6f}};
   int best = -1;
@@ -323,12 +359,18 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
 }  // namespace
 
 bool gemm_mfma_supported(int dtype, const GemmDesc& d) {
-  if (dtype != 1 || d.nz1 * d.nz2 != 1 || d.causal != kCausalNone) return false;
+  if (dtype != 1) return false;
   if (d.M % 128 || d.N % 128 || d.K % kBK || d.K < kBK) return false;
+  if (d.causal == kCausalOutLower && d.M != d.N) return false;
+  if ((d.causal == kCausalKLeM || d.causal == kCausalKGeM) && (d.M != d.K || d.bias != nullptr)) return false;
   const bool a_k = d.a_sk == 1, a_mn = d.a_sm == 1;
   const bool b_k = d.b_sk == 1, b_mn = d.b_sn == 1;
   if (!(a_k || a_mn) || !(b_k || b_mn)) return false;
   if ((a_k ? d.a_sm : d.a_sk) % 8 || (b_k ? d.b_sn : d.b_sk) % 8 || d.c_sm % 4) return false;
+  if (d.a_sz1 % 8 || d.a_sz2 % 8 || d.b_sz1 % 8 || d.b_sz2 % 8 || d.c_sz1 % 4 || d.c_sz2 % 4) return false;
+  if ((reinterpret_cast<uintptr_t>(d.A) | reinterpret_cast<uintptr_t>(d.B)) & 15) return false;
+  if (reinterpret_cast<uintptr_t>(d.C) & 7) return false;
+  if (d.bias != nullptr && (reinterpret_cast<uintptr_t>(d.bias) & 7)) return false;
   return true;
 }
 
@@ -340,6 +382,9 @@ hipError_t gemm_mfma(const GemmDesc& d, hipStream_t st) {
   a.C = static_cast<bf16_t*>(d.C); a.ldc = d.c_sm;
   a.bias = static_cast<const bf16_t*>(d.bias);
   a.M = d.M; a.N = d.N; a.K = d.K;
+  a.a_z1 = d.a_sz1; a.a_z2 = d.a_sz2; a.b_z1 = d.b_sz1; a.b_z2 = d.b_sz2;
+  a.c_z1 = d.c_sz1; a.c_z2 = d.c_sz2;
+  a.nz = d.nz1 * d.nz2; a.nz2 = d.nz2; a.causal = d.causal;
   if (a_k && b_k) return launch_tiles<true, true>(a, st);
   if (a_k && !b_k) return launch_tiles<true, false>(a, st);
   if (!a_k && b_k) return launch_tiles<false, true>(a, st);

@@ -27,6 +27,9 @@ SMALL = {
     # multiples of 128 but not of 256: the smaller matrix-core tiles
     "tiles128_bf16": synth.LayerConfig(synth.BF16, 640, 3, 128, 1152, 128, 3, tp_size=1,
                                        dropout_p=0.1, seed=4, layer_id=7),
+    # sequence of two 256-tiles: the large score tiles and multi-slab causal contractions
+    "tiles256_bf16": synth.LayerConfig(synth.BF16, 256, 2, 128, 256, 512, 1, tp_size=1,
+                                       dropout_p=0.1, seed=6, layer_id=3),
     "C1": synth.CONFIGS["C1"],
     "nodrop_bf16": synth.LayerConfig(synth.BF16, 256, 2, 64, 512, 128, 1, dropout_p=0.0),
     "minimal_f32": synth.LayerConfig(synth.F32, 8, 1, 8, 8, 8, 1, dropout_p=0.5, seed=9),
@@ -93,7 +96,7 @@ def test_store_all_forward_and_backward_match_oracle(name):
     layer.close()
 
 
-@pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16", "tiles128_bf16"])
+@pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16", "tiles128_bf16", "tiles256_bf16"])
 def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
     cfg = SMALL[name]
     params = synth.make_params(cfg, random_ln=True)
