@@ -4,6 +4,7 @@
 // consecutive vectors.  Column sums are two fixed-order stages (per row-block
 // partials, then a serial sum over row-blocks), so results are deterministic.
 #include "dropout_host.h"
+#include "reduce_partials.h"
 
 namespace lynx {
 namespace {
@@ -99,25 +100,13 @@ __global__ void __launch_bounds__(kThreads) rows_colsum_kernel(Op op, int rows, 
   store8(p, acc);
 }
 
-template <typename T>
-__global__ void __launch_bounds__(kThreads) colsum_finalize_kernel(const float* __restrict__ partial,
-                                                                   T* __restrict__ out, int nparts,
-                                                                   int cols) {
-  const int c = blockIdx.x * kThreads + threadIdx.x;
-  if (c >= cols) return;
-  float s = 0.f;
-  for (int r = 0; r < nparts; ++r) s += partial[static_cast<size_t>(r) * cols + c];
-  store1(out + c, s);
-}
-
 template <typename T, typename Op>
 hipError_t launch_rows_colsum(Op op, T* dbias, float* scratch, int rows, int cols, hipStream_t st) {
   const int nvec = cols / 8;
   const int nrb = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
   dim3 grid((nvec + kThreads - 1) / kThreads, nrb);
   hipLaunchKernelGGL((rows_colsum_kernel<Op>), grid, dim3(kThreads), 0, st, op, rows, cols, scratch);
-  hipLaunchKernelGGL((colsum_finalize_kernel<T>), dim3((cols + kThreads - 1) / kThreads),
-                     dim3(kThreads), 0, st, scratch, dbias, nrb, cols);
+  launch_reduce_partials<T>(scratch, dbias, nullptr, nullptr, nrb, cols, st);
   return hipGetLastError();
 }
 

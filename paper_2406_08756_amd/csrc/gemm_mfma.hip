@@ -188,17 +188,22 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   const long long a_step = A_KMAJOR ? kBK : kBK * g.lda;  // elements per slab
   const long long b_step = B_KMAJOR ? kBK : kBK * g.ldb;
 
-  auto issue_slab = [&](int kt) {  // slab kt -> ring stage kt % kStages
+  // j-th direct load of slab kt (A pieces first, then B) -> ring stage kt % kStages
+  auto issue_load = [&](int kt, int j) {
     bf16_t* sa = smem + (kt & (kStages - 1)) * kStageElems;
-    bf16_t* sb = sa + SA::kElems;
-#pragma unroll
-    for (int j = 0; j < SA::kLoadsPerWave; ++j)
+    if (j < SA::kLoadsPerWave) {
       __builtin_amdgcn_global_load_lds((global_void_ptr)(ga[j] + kt * a_step),
                                        (lds_void_ptr)(sa + SA::lds_offset(wave, j)), 16, 0, 0);
+    } else {
+      const int jb = j - SA::kLoadsPerWave;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(gb[jb] + kt * b_step),
+                                       (lds_void_ptr)(sa + SA::kElems + SB::lds_offset(wave, jb)), 16,
+                                       0, 0);
+    }
+  };
+  auto issue_slab = [&](int kt) {
 #pragma unroll
-    for (int j = 0; j < SB::kLoadsPerWave; ++j)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(gb[j] + kt * b_step),
-                                       (lds_void_ptr)(sb + SB::lds_offset(wave, j)), 16, 0, 0);
+    for (int j = 0; j < kLoads; ++j) issue_load(kt, j);
   };
 
   floatx16_t acc[TN][TM];
@@ -229,26 +234,34 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
     for (int i = 0; i < TN; ++i) fb0[i] = SB::fragment(sb, wn0 + 32 * i, 0, lane);
   }
 
-  // One slab: [refill ring] [read 2nd-half fragments] [MFMA 1st half] [next slab landed?]
-  // [barrier] [read next slab's 1st-half fragments] [MFMA 2nd half].  `steady` = three
-  // more slabs exist, so the refill and the waits need no conditions.
+  // One slab = two halves of TM x TN MFMAs.  The side work is spread between the MFMAs
+  // so the matrix pipe never waits for an issue burst: during the first half the
+  // second-half fragments are read and the ring stage that every wavefront finished
+  // before the last barrier is refilled; then [next slab landed?] [barrier]; during the
+  // second half the next slab's first-half fragments are read.  `steady` = three more
+  // slabs exist, so the refill and the waits need no conditions.
+  constexpr int kMfmas = TM * TN;
+  constexpr int kSide1 = TM + TN + kLoads;               // side operations of the first half
+  constexpr int kPer1 = (kSide1 + kMfmas - 1) / kMfmas;  // per MFMA
+  constexpr int kPer2 = (TM + TN + kMfmas - 1) / kMfmas;
   auto slab_step = [&](int kt, auto steady_tag) {
     constexpr bool steady = decltype(steady_tag)::value;
     const bf16_t* sa = smem + (kt & (kStages - 1)) * kStageElems;
     const bf16_t* sb = sa + SA::kElems;
-    // refill the stage every wavefront finished reading before the last barrier
-    if (steady || kt + 3 < nk) issue_slab(kt + 3);
+    const bool refill = steady || kt + 3 < nk;
 #pragma unroll
-    for (int j = 0; j < TM; ++j) fa1[j] = SA::fragment(sa, wm0 + 32 * j, 1, lane);
+    for (int m = 0; m < kMfmas; ++m) {
+      const int i = m / TM, j = m % TM;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < TN; ++i) fb1[i] = SB::fragment(sb, wn0 + 32 * i, 1, lane);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-      for (int j = 0; j < TM; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int u = 0; u < kPer1; ++u) {
+        const int op = m * kPer1 + u;
+        if (op < TM) fa1[op] = SA::fragment(sa, wm0 + 32 * op, 1, lane);
+        else if (op < TM + TN) fb1[op - TM] = SB::fragment(sb, wn0 + 32 * (op - TM), 1, lane);
+        else if (op < kSide1) { if (refill) issue_load(kt + 3, op - TM - TN); }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // the next slab must have landed (two newer ones may still be in flight), and all
     // of this wavefront's reads of the current slab must be complete
     if (steady || kt + 3 < nk) wait_vmcnt<2 * kLoads>();
@@ -256,22 +269,24 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
     else wait_vmcnt<0>();
     wait_lgkmcnt0();
     block_barrier();
-    if (steady || kt + 1 < nk) {
-      const bf16_t* na = smem + ((kt + 1) & (kStages - 1)) * kStageElems;
-      const bf16_t* nb = na + SA::kElems;
+    const bool more = steady || kt + 1 < nk;
+    const bf16_t* na = smem + ((kt + 1) & (kStages - 1)) * kStageElems;
+    const bf16_t* nb = na + SA::kElems;
 #pragma unroll
-      for (int j = 0; j < TM; ++j) fa0[j] = SA::fragment(na, wm0 + 32 * j, 0, lane);
+    for (int m = 0; m < kMfmas; ++m) {
+      const int i = m / TM, j = m % TM;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
 #pragma unroll
-      for (int i = 0; i < TN; ++i) fb0[i] = SB::fragment(nb, wn0 + 32 * i, 0, lane);
+      for (int u = 0; u < kPer2; ++u) {
+        const int op = m * kPer2 + u;
+        if (more) {
+          if (op < TM) fa0[op] = SA::fragment(na, wm0 + 32 * op, 0, lane);
+          else if (op < TM + TN) fb0[op - TM] = SB::fragment(nb, wn0 + 32 * (op - TM), 0, lane);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-      for (int j = 0; j < TM; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_lgkmcnt0();  // long since complete; tells the compiler nothing is pending at the loop top
+    wait_lgkmcnt0();  // tells the compiler nothing is pending at the loop top
   };
   wait_lgkmcnt0();
   int kt = 0;

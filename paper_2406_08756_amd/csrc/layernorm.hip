@@ -6,6 +6,7 @@
 // visits, and are then reduced over workgroups in a second fixed-order stage.
 #include "device_common.h"
 #include "kernels.h"
+#include "reduce_partials.h"
 
 namespace lynx {
 namespace {
@@ -144,21 +145,6 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
   }
 }
 
-template <typename T>
-__global__ void __launch_bounds__(256)
-layernorm_bwd_finalize_kernel(const float* __restrict__ part_dg, const float* __restrict__ part_db,
-                              T* __restrict__ dgamma, T* __restrict__ dbeta, int nparts, int cols) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= cols) return;
-  float a = 0.f, b = 0.f;
-  for (int r = 0; r < nparts; ++r) {
-    a += part_dg[static_cast<size_t>(r) * cols + c];
-    b += part_db[static_cast<size_t>(r) * cols + c];
-  }
-  store1(dgamma + c, a);
-  store1(dbeta + c, b);
-}
-
 int bwd_blocks(int rows) { return rows < kBwdMaxBlocks ? rows : kBwdMaxBlocks; }
 
 }  // namespace
@@ -221,13 +207,12 @@ hipError_t layernorm_bwd(int dtype, const void* dy, const void* x, const float* 
   else if (nc <= 3) { CALL(3); }
   else { CALL(4); }
 #undef CALL
-  const dim3 fgrid((cols + 255) / 256);
   if (dtype == 1)
-    hipLaunchKernelGGL((layernorm_bwd_finalize_kernel<bf16_t>), fgrid, dim3(256), 0, st, part_dg,
-                       part_db, static_cast<bf16_t*>(dgamma), static_cast<bf16_t*>(dbeta), nb, cols);
+    launch_reduce_partials<bf16_t>(part_dg, static_cast<bf16_t*>(dgamma), part_db,
+                                   static_cast<bf16_t*>(dbeta), nb, cols, st);
   else
-    hipLaunchKernelGGL((layernorm_bwd_finalize_kernel<float>), fgrid, dim3(256), 0, st, part_dg,
-                       part_db, static_cast<float*>(dgamma), static_cast<float*>(dbeta), nb, cols);
+    launch_reduce_partials<float>(part_dg, static_cast<float*>(dgamma), part_db,
+                                  static_cast<float*>(dbeta), nb, cols, st);
   return hipGetLastError();
 }
 
