@@ -76,19 +76,27 @@ def phase_flops(cfg, retain_mask):
 
 
 def cpu_baseline(cfg, retain_name):
-    """The fp64 oracle as it stands, timed on the host cores on micro-batch 1
-    (its cost is linear in the micro-batch size)."""
+    """The fp64 oracle as it stands, timed on the host cores on a bounded
+    sample: as many micro-batch elements as fit in roughly 20 s (its cost is
+    linear in the micro-batch size; one element is timed first to decide)."""
     import numpy as np
     import lynx_synth as synth
     from oracle import lynx_oracle as orc
-    small = cfg.with_(micro_batch=1)
-    params = synth.make_params(small)
-    X, dOUT = synth.make_x(small), synth.make_dout(small)
-    t0 = time.perf_counter()
-    acts = orc.layer_forward(small, params, X)
-    t1 = time.perf_counter()
-    orc.layer_backward(small, params, acts, dOUT)
-    t2 = time.perf_counter()
+    def timed(nb):
+        small = cfg.with_(micro_batch=nb)
+        params = synth.make_params(small)
+        X, dOUT = synth.make_x(small), synth.make_dout(small)
+        t0 = time.perf_counter()
+        acts = orc.layer_forward(small, params, X)
+        t1 = time.perf_counter()
+        orc.layer_backward(small, params, acts, dOUT)
+        t2 = time.perf_counter()
+        return small, t0, t1, t2
+
+    small, t0, t1, t2 = timed(1)
+    nb = max(1, min(cfg.micro_batch, int(20.0 / max(t2 - t0, 1e-3))))
+    if nb > 1:
+        small, t0, t1, t2 = timed(nb)
     fwd, rec, bwd = phase_flops(small, POLICIES[retain_name])
     # the oracle has no policy machinery: regeneration costs what those forward
     # operators cost, so scale the measured forward by the share regenerated
@@ -99,8 +107,9 @@ def cpu_baseline(cfg, retain_name):
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": (rec + bwd) / sec / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": "micro_batch 1 of %d; fp64 numpy oracle forward %.1f s + backward %.1f s; "
-                      "regeneration priced as its share of forward FLOPs" % (cfg.micro_batch, t1 - t0, t2 - t1)}
+            "sample": "micro_batch %d of %d; fp64 numpy oracle forward %.1f s + backward %.1f s; "
+                      "regeneration priced as its share of forward FLOPs" % (
+                          small.micro_batch, cfg.micro_batch, t1 - t0, t2 - t1)}
 
 
 def main():
