@@ -132,3 +132,10 @@ def make_x(cfg: LayerConfig, seed: int = 1) -> np.ndarray:
 
 def make_dout(cfg: LayerConfig, seed: int = 2) -> np.ndarray:
     return _store(_normal(seed, (cfg.tokens, cfg.hidden), 1.0), cfg.dtype)
+
+
+def c5_retain_masks(policy_seed: int = 0, layers: int = C5_LAYERS):
+    """Per-layer retain masks of the six-layer slice: bits 1..13 drawn from a
+    seeded generator, bit 0 (the layer input, always the checkpoint) set."""
+    rng = np.random.Generator(np.random.Philox(1_000_003 + policy_seed))
+    return [int(m) | 1 for m in rng.integers(0, 1 << 14, size=layers)]

@@ -20,7 +20,8 @@
 //   MN-major slab [32][mn]: chunk ^= (k & 3) << 1, read with the transposing
 //     LDS read (ds_read_b64_tr_b16) that hands each lane four consecutive k.
 // The product is formed transposed (B fragment as the first MFMA operand) so
-// each lane ends with four consecutive n of one row m and stores 8 bytes.
+// each lane ends with four consecutive n of one row m; the epilogue passes the
+// tile through LDS and stores whole rows, 16 bytes per lane.
 #include <type_traits>
 
 #include "device_common.h"
@@ -293,26 +294,43 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   for (; kt + 3 < nk; ++kt) slab_step(kt, std::true_type{});
   for (; kt < nk; ++kt) slab_step(kt, std::false_type{});
 
-  // acc[i][j][r]: n = wn0 + 32 i + 8 (r/4) + 4 (lane/32) + r%4,  m = wm0 + 32 j + lane%32
+  // Epilogue.  acc[i][j][r] is the element n = wn0 + 32 i + 8 (r/4) + 4 (lane/32) + r%4,
+  // m = wm0 + 32 j + lane%32.  Each wavefront rounds its quarter tile (+ bias) to bf16 into
+  // its own region of the now idle LDS ring and writes it out as whole rows, 16 bytes per
+  // lane.  16-byte chunks of LDS row r are XORed with r so both the 8-byte writes and the
+  // 16-byte row reads spread over all banks.
+  block_barrier();  // every wavefront is done with the ring (no load is in flight any more)
+  constexpr int kRowChunks = WN / 8;
+  bf16_t* stage = smem + wave * (WM * WN);
 #pragma unroll
   for (int i = 0; i < TN; ++i)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int n = n0 + wn0 + 32 * i + 8 * q + 4 * (lane >> 5);
+      const int nl = 32 * i + 8 * q + 4 * (lane >> 5);
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
       if (g.bias != nullptr) {
-        const uint2 braw = *reinterpret_cast<const uint2*>(g.bias + n);
+        const uint2 braw = *reinterpret_cast<const uint2*>(g.bias + n0 + wn0 + nl);
         bv[0] = bf16_lo(braw.x); bv[1] = bf16_hi(braw.x); bv[2] = bf16_lo(braw.y); bv[3] = bf16_hi(braw.y);
       }
 #pragma unroll
       for (int j = 0; j < TM; ++j) {
-        const int m = m0 + wm0 + 32 * j + (lane & 31);
+        const int ml = 32 * j + (lane & 31);
         uint2 o;
         o.x = pack_bf16(acc[i][j][4 * q + 0] + bv[0], acc[i][j][4 * q + 1] + bv[1]);
         o.y = pack_bf16(acc[i][j][4 * q + 2] + bv[2], acc[i][j][4 * q + 3] + bv[3]);
-        *reinterpret_cast<uint2*>(Cbase + static_cast<long long>(m) * g.ldc + n) = o;
+        const int chunk = (nl >> 3) ^ (ml & (kRowChunks - 1));
+        *reinterpret_cast<uint2*>(stage + ml * WN + chunk * 8 + (nl & 7)) = o;
       }
     }
+  constexpr int kRowsPerStore = kWave / kRowChunks;
+  bf16_t* cw = Cbase + static_cast<long long>(m0 + wm0) * g.ldc + n0 + wn0;
+#pragma unroll
+  for (int t = 0; t < WM / kRowsPerStore; ++t) {
+    const int r = t * kRowsPerStore + lane / kRowChunks;
+    const int lc = lane % kRowChunks;
+    const uint4 v = *reinterpret_cast<const uint4*>(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3));
+    *reinterpret_cast<uint4*>(cw + static_cast<long long>(r) * g.ldc + lc * 8) = v;
+  }
 }
 
 template <bool AK, bool BK_, int BM, int BN>
@@ -381,10 +399,10 @@ bool gemm_mfma_supported(int dtype, const GemmDesc& d) {
   const bool a_k = d.a_sk == 1, a_mn = d.a_sm == 1;
   const bool b_k = d.b_sk == 1, b_mn = d.b_sn == 1;
   if (!(a_k || a_mn) || !(b_k || b_mn)) return false;
-  if ((a_k ? d.a_sm : d.a_sk) % 8 || (b_k ? d.b_sn : d.b_sk) % 8 || d.c_sm % 4) return false;
-  if (d.a_sz1 % 8 || d.a_sz2 % 8 || d.b_sz1 % 8 || d.b_sz2 % 8 || d.c_sz1 % 4 || d.c_sz2 % 4) return false;
+  if ((a_k ? d.a_sm : d.a_sk) % 8 || (b_k ? d.b_sn : d.b_sk) % 8 || d.c_sm % 8) return false;
+  if (d.a_sz1 % 8 || d.a_sz2 % 8 || d.b_sz1 % 8 || d.b_sz2 % 8 || d.c_sz1 % 8 || d.c_sz2 % 8) return false;
   if ((reinterpret_cast<uintptr_t>(d.A) | reinterpret_cast<uintptr_t>(d.B)) & 15) return false;
-  if (reinterpret_cast<uintptr_t>(d.C) & 7) return false;
+  if (reinterpret_cast<uintptr_t>(d.C) & 15) return false;
   if (d.bias != nullptr && (reinterpret_cast<uintptr_t>(d.bias) & 7)) return false;
   return true;
 }
