@@ -47,15 +47,16 @@ class GpuLayer:
             self.B.lynx_layer_destroy(self.handle)
             self.handle = None
 
-    def forward(self, x_np, retain_mask, step=0):
-        self.x = to_device(x_np, self.cfg.dtype)
+    def forward(self, x, retain_mask, step=0):
+        """x: numpy array (uploaded) or a device tensor of the storage dtype (borrowed)."""
+        self.x = x if isinstance(x, torch.Tensor) else to_device(x, self.cfg.dtype)
         self.B.lynx_layer_forward(self.handle, self.x, self.out, retain_mask, step)
 
     def recompute(self, segment):
         self.B.lynx_recompute(self.handle, segment)
 
-    def backward(self, dout_np):
-        self.dout = to_device(dout_np, self.cfg.dtype)
+    def backward(self, dout):
+        self.dout = dout if isinstance(dout, torch.Tensor) else to_device(dout, self.cfg.dtype)
         self.B.lynx_layer_backward(self.handle, self.dout, self.dx, self.grads)
 
     def activation_raw(self, act_id) -> torch.Tensor | None:
