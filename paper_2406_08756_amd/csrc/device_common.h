@@ -116,4 +116,21 @@ __device__ __forceinline__ uint32_t dropout_keep8(const DropoutKey& k, uint64_t 
   return m;
 }
 
+// v[l] = keep(l) ? v[l] * scale : 0 for the 8 elements of one group, straight from
+// the 16-bit fields (no intermediate bit mask).
+__device__ __forceinline__ void dropout_apply8(const DropoutKey& k, uint64_t group, float (&v)[8]) {
+  const uint4 w = philox4x32_10(static_cast<uint32_t>(group), static_cast<uint32_t>(group >> 32),
+                                k.stream0, k.stream1, k.key0, k.key1);
+  const uint32_t t = k.threshold;
+  const float s = k.scale;
+  v[0] = ((w.x & 0xFFFFu) >= t) ? v[0] * s : 0.0f;
+  v[1] = ((w.x >> 16) >= t) ? v[1] * s : 0.0f;
+  v[2] = ((w.y & 0xFFFFu) >= t) ? v[2] * s : 0.0f;
+  v[3] = ((w.y >> 16) >= t) ? v[3] * s : 0.0f;
+  v[4] = ((w.z & 0xFFFFu) >= t) ? v[4] * s : 0.0f;
+  v[5] = ((w.z >> 16) >= t) ? v[5] * s : 0.0f;
+  v[6] = ((w.w & 0xFFFFu) >= t) ? v[6] * s : 0.0f;
+  v[7] = ((w.w >> 16) >= t) ? v[7] * s : 0.0f;
+}
+
 }  // namespace lynx

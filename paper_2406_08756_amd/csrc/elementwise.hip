@@ -10,7 +10,7 @@ namespace lynx {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsPerBlock = 64;  // rows folded into one column-sum partial
+constexpr int kRowsPerBlock = 32;  // rows folded into one column-sum partial
 
 // tanh-form GeLU (operator 11) and its derivative.
 constexpr float kKappa = 0.7978845608028654f;  // sqrt(2/pi)
@@ -42,70 +42,126 @@ __global__ void __launch_bounds__(kThreads) gelu_fwd_kernel(const T* __restrict_
 }
 
 // ---- per-element functors used with the column-sum frame ------------------
+// apply(a, b, group, out): a, b = 8 elements of the one or two inputs, group =
+// flat element index / 8; out = the 8 results, already rounded to storage.
 template <typename T>
-struct GeluBwdOp {
-  const T* dg; const T* u; T* du;
-  __device__ __forceinline__ void operator()(size_t off, size_t, float (&out)[8]) const {
-    float a[8], b[8];
-    load8(dg + off, a);
-    load8(u + off, b);
+struct GeluBwdOp {  // du = dg * gelu'(u)
+  static constexpr int kInputs = 2;
+  static constexpr bool kStores = true;
+  __device__ __forceinline__ void apply(const float (&a)[8], const float (&b)[8], size_t,
+                                        float (&out)[8]) const {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = round_to_storage(a[i] * gelu_grad_f(b[i]), du);
-    store8(du + off, out);
+    for (int i = 0; i < 8; ++i) out[i] = round_to_storage(a[i] * gelu_grad_f(b[i]), static_cast<T*>(nullptr));
   }
 };
 
 template <typename T>
-struct DropoutBwdOp {
-  const T* dout; T* din; DropoutKey key;
-  __device__ __forceinline__ void operator()(size_t off, size_t group, float (&out)[8]) const {
-    float a[8];
-    load8(dout + off, a);
-    const uint32_t keep = dropout_keep8(key, group);
+struct DropoutBwdOp {  // din = keep * dout / (1 - p)
+  static constexpr int kInputs = 1;
+  static constexpr bool kStores = true;
+  DropoutKey key;
+  __device__ __forceinline__ void apply(const float (&a)[8], const float (&)[8], size_t group,
+                                        float (&out)[8]) const {
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      out[i] = round_to_storage(((keep >> i) & 1u) ? a[i] * key.scale : 0.0f, din);
-    store8(din + off, out);
+    for (int i = 0; i < 8; ++i) out[i] = a[i];
+    dropout_apply8(key, group, out);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = round_to_storage(out[i], static_cast<T*>(nullptr));
   }
 };
 
 template <typename T>
 struct IdentityOp {
-  const T* x;
-  __device__ __forceinline__ void operator()(size_t off, size_t, float (&out)[8]) const {
-    load8(x + off, out);
+  static constexpr int kInputs = 1;
+  static constexpr bool kStores = false;
+  __device__ __forceinline__ void apply(const float (&a)[8], const float (&)[8], size_t,
+                                        float (&out)[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = a[i];
   }
 };
 
-// Frame: block (bx, by) covers vectors [bx*256, +256) of rows [by*64, +64);
-// thread applies op to its vector in each row and accumulates the 8 columns.
-template <typename Op>
-__global__ void __launch_bounds__(kThreads) rows_colsum_kernel(Op op, int rows, int cols,
-                                                               float* __restrict__ partial) {
-  const int vec = blockIdx.x * kThreads + threadIdx.x;
-  const int nvec = cols >> 3;
-  if (vec >= nvec) return;
-  const int r0 = blockIdx.y * kRowsPerBlock;
-  const int r1 = min(rows, r0 + kRowsPerBlock);
+// 8 storage elements as loaded, before conversion (keeps loads cheap to batch).
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> { uint4 v; };
+template <> struct Raw8<float> { float4 lo, hi; };
+__device__ __forceinline__ void load_raw(const bf16_t* p, Raw8<bf16_t>& r) {
+  r.v = *reinterpret_cast<const uint4*>(p);
+}
+__device__ __forceinline__ void load_raw(const float* p, Raw8<float>& r) {
+  r.lo = *reinterpret_cast<const float4*>(p);
+  r.hi = *reinterpret_cast<const float4*>(p + 4);
+}
+__device__ __forceinline__ void unpack(const Raw8<bf16_t>& r, float (&v)[8]) {
+  v[0] = bf16_lo(r.v.x); v[1] = bf16_hi(r.v.x); v[2] = bf16_lo(r.v.y); v[3] = bf16_hi(r.v.y);
+  v[4] = bf16_lo(r.v.z); v[5] = bf16_hi(r.v.z); v[6] = bf16_lo(r.v.w); v[7] = bf16_hi(r.v.w);
+}
+__device__ __forceinline__ void unpack(const Raw8<float>& r, float (&v)[8]) {
+  v[0] = r.lo.x; v[1] = r.lo.y; v[2] = r.lo.z; v[3] = r.lo.w;
+  v[4] = r.hi.x; v[5] = r.hi.y; v[6] = r.hi.z; v[7] = r.hi.w;
+}
+
+// Frame: a workgroup owns a tile of kRowsPerBlock rows x 64 vectors (512 columns):
+// wavefront w takes rows w, w + 4, ... of the tile, lane l the l-th vector, so every
+// wavefront access is 1 KB contiguous and a thread's column stays fixed.  All of a
+// thread's loads are issued before its first store; the four wavefronts' column sums
+// are added in a fixed order through LDS.  Many small workgroups keep enough
+// wavefronts resident to overlap the Philox / GeLU arithmetic with the memory traffic.
+constexpr int kRowsPerThread = kRowsPerBlock / (kThreads / kWave);
+template <typename T, typename Op>
+__global__ void __launch_bounds__(kThreads)
+rows_colsum_kernel(Op op, const T* __restrict__ in0, const T* __restrict__ in1, T* __restrict__ outp,
+                   int rows, int cols, float* __restrict__ partial) {
+  __shared__ float sm[kThreads / kWave][kWave][8];
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+  const int vec = blockIdx.x * kWave + lane;
+  const bool active = vec < (cols >> 3);
+  const int r0 = blockIdx.y * kRowsPerBlock + w;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-  for (int r = r0; r < r1; ++r) {
-    const size_t off = static_cast<size_t>(r) * cols + static_cast<size_t>(vec) * 8;
-    float v[8];
-    op(off, off >> 3, v);
+  if (active) {
+    Raw8<T> ra[kRowsPerThread], rb[Op::kInputs == 2 ? kRowsPerThread : 1];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] += v[i];
+    for (int k = 0; k < kRowsPerThread; ++k) {
+      const int r = r0 + k * (kThreads / kWave);
+      if (r < rows) {
+        const size_t off = static_cast<size_t>(r) * cols + static_cast<size_t>(vec) * 8;
+        load_raw(in0 + off, ra[k]);
+        if (Op::kInputs == 2) load_raw(in1 + off, rb[Op::kInputs == 2 ? k : 0]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kRowsPerThread; ++k) {
+      const int r = r0 + k * (kThreads / kWave);
+      if (r < rows) {
+        const size_t off = static_cast<size_t>(r) * cols + static_cast<size_t>(vec) * 8;
+        float a[8], b[8] = {}, v[8];
+        unpack(ra[k], a);
+        if (Op::kInputs == 2) unpack(rb[Op::kInputs == 2 ? k : 0], b);
+        op.apply(a, b, off >> 3, v);
+        if (Op::kStores) store8(outp + off, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += v[i];
+      }
+    }
   }
-  float* p = partial + static_cast<size_t>(blockIdx.y) * cols + static_cast<size_t>(vec) * 8;
-  store8(p, acc);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sm[w][lane][i] = acc[i];
+  __syncthreads();
+  if (w == 0 && active) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = (sm[0][lane][i] + sm[1][lane][i]) + (sm[2][lane][i] + sm[3][lane][i]);
+    store8(partial + static_cast<size_t>(blockIdx.y) * cols + static_cast<size_t>(vec) * 8, acc);
+  }
 }
 
 template <typename T, typename Op>
-hipError_t launch_rows_colsum(Op op, T* dbias, float* scratch, int rows, int cols, hipStream_t st) {
+hipError_t launch_rows_colsum(Op op, const T* in0, const T* in1, T* outp, T* dbias, float* scratch,
+                              int rows, int cols, hipStream_t st) {
   const int nvec = cols / 8;
   const int nrb = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
-  dim3 grid((nvec + kThreads - 1) / kThreads, nrb);
-  hipLaunchKernelGGL((rows_colsum_kernel<Op>), grid, dim3(kThreads), 0, st, op, rows, cols, scratch);
+  const dim3 grid((nvec + kWave - 1) / kWave, nrb);
+  hipLaunchKernelGGL((rows_colsum_kernel<T, Op>), grid, dim3(kThreads), 0, st, op, in0, in1, outp,
+                     rows, cols, scratch);
   launch_reduce_partials<T>(scratch, dbias, nullptr, nullptr, nrb, cols, st);
   return hipGetLastError();
 }
@@ -123,9 +179,11 @@ bias_dropout_add_kernel(const T* __restrict__ in, const T* __restrict__ bias,
   load8(in + off, a);
   load8(bias + c, b);
   load8(res + off, r);
-  const uint32_t keep = dropout_keep8(key, v);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) r[i] += ((keep >> i) & 1u) ? (a[i] + b[i]) * key.scale : 0.0f;
+  for (int i = 0; i < 8; ++i) a[i] += b[i];
+  dropout_apply8(key, v, a);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] += a[i];
   store8(out + off, r);
 }
 
@@ -163,13 +221,13 @@ hipError_t gelu_fwd(int dtype, const void* u, void* g, size_t n, hipStream_t st)
 hipError_t gelu_bwd(int dtype, const void* dg, const void* u, void* du, void* dbias, float* scratch,
                     int rows, int cols, hipStream_t st) {
   if (dtype == 1) {
-    GeluBwdOp<bf16_t> op{static_cast<const bf16_t*>(dg), static_cast<const bf16_t*>(u),
-                         static_cast<bf16_t*>(du)};
-    return launch_rows_colsum(op, static_cast<bf16_t*>(dbias), scratch, rows, cols, st);
+    return launch_rows_colsum(GeluBwdOp<bf16_t>{}, static_cast<const bf16_t*>(dg),
+                              static_cast<const bf16_t*>(u), static_cast<bf16_t*>(du),
+                              static_cast<bf16_t*>(dbias), scratch, rows, cols, st);
   }
-  GeluBwdOp<float> op{static_cast<const float*>(dg), static_cast<const float*>(u),
-                      static_cast<float*>(du)};
-  return launch_rows_colsum(op, static_cast<float*>(dbias), scratch, rows, cols, st);
+  return launch_rows_colsum(GeluBwdOp<float>{}, static_cast<const float*>(dg),
+                            static_cast<const float*>(u), static_cast<float*>(du),
+                            static_cast<float*>(dbias), scratch, rows, cols, st);
 }
 
 hipError_t bias_dropout_add_fwd(int dtype, const void* in, const void* bias, const void* res,
@@ -193,21 +251,25 @@ hipError_t dropout_bwd(int dtype, const void* dout, void* din, void* dbias, floa
                        int cols, int site, DropoutParams dp, hipStream_t st) {
   const DropoutKey key = make_dropout_key(dp, site);
   if (dtype == 1) {
-    DropoutBwdOp<bf16_t> op{static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(din), key};
-    return launch_rows_colsum(op, static_cast<bf16_t*>(dbias), scratch, rows, cols, st);
+    return launch_rows_colsum(DropoutBwdOp<bf16_t>{key}, static_cast<const bf16_t*>(dout),
+                              static_cast<const bf16_t*>(nullptr), static_cast<bf16_t*>(din),
+                              static_cast<bf16_t*>(dbias), scratch, rows, cols, st);
   }
-  DropoutBwdOp<float> op{static_cast<const float*>(dout), static_cast<float*>(din), key};
-  return launch_rows_colsum(op, static_cast<float*>(dbias), scratch, rows, cols, st);
+  return launch_rows_colsum(DropoutBwdOp<float>{key}, static_cast<const float*>(dout),
+                            static_cast<const float*>(nullptr), static_cast<float*>(din),
+                            static_cast<float*>(dbias), scratch, rows, cols, st);
 }
 
 hipError_t column_sum(int dtype, const void* x, void* dbias, float* scratch, int rows, int cols,
                       hipStream_t st) {
   if (dtype == 1) {
-    IdentityOp<bf16_t> op{static_cast<const bf16_t*>(x)};
-    return launch_rows_colsum(op, static_cast<bf16_t*>(dbias), scratch, rows, cols, st);
+    return launch_rows_colsum(IdentityOp<bf16_t>{}, static_cast<const bf16_t*>(x),
+                              static_cast<const bf16_t*>(nullptr), static_cast<bf16_t*>(nullptr),
+                              static_cast<bf16_t*>(dbias), scratch, rows, cols, st);
   }
-  IdentityOp<float> op{static_cast<const float*>(x)};
-  return launch_rows_colsum(op, static_cast<float*>(dbias), scratch, rows, cols, st);
+  return launch_rows_colsum(IdentityOp<float>{}, static_cast<const float*>(x),
+                            static_cast<const float*>(nullptr), static_cast<float*>(nullptr),
+                            static_cast<float*>(dbias), scratch, rows, cols, st);
 }
 
 hipError_t dropout_mask_hidden(uint8_t* out, size_t n, int site, DropoutParams dp, hipStream_t st) {

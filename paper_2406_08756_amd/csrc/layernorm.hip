@@ -68,28 +68,33 @@ layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
   }
 }
 
-// Block-wide sum of two values; every thread gets both totals.
-__device__ __forceinline__ void block_sum2(float& a, float& b, float* smem) {
-  a = wave_sum(a);
-  b = wave_sum(b);
+// Block-wide sums of four values; every thread gets all totals.  The combination
+// order is fixed.
+__device__ __forceinline__ void block_sum4(float (&v)[4], float* smem) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = wave_sum(v[i]);
   const int w = threadIdx.x >> 6;
   __syncthreads();  // previous use of smem is over
   if ((threadIdx.x & (kWave - 1)) == 0) {
-    smem[w] = a;
-    smem[4 + w] = b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) smem[4 * i + w] = v[i];
   }
   __syncthreads();
-  a = (smem[0] + smem[1]) + (smem[2] + smem[3]);
-  b = (smem[4] + smem[5]) + (smem[6] + smem[7]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    v[i] = (smem[4 * i] + smem[4 * i + 1]) + (smem[4 * i + 2] + smem[4 * i + 3]);
 }
 
+// Two rows per iteration: all loads of both rows (dy, x, residual gradient) are
+// issued before the reductions, which doubles the bytes in flight per workgroup
+// and halves the number of workgroup barriers per row.
 template <typename T, int NC>
 __global__ void __launch_bounds__(kBwdThreads)
 layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                      const float* __restrict__ mean, const float* __restrict__ rstd,
                      const T* __restrict__ gamma, const T* dres, T* dx_out,
                      float* __restrict__ part_dg, float* __restrict__ part_db, int rows, int cols) {
-  __shared__ float smem[8];
+  __shared__ float smem[16];
   float g[NC][8], adg[NC][8], adb[NC][8];
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
@@ -99,39 +104,62 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
     for (int k = 0; k < 8; ++k) { adg[c][k] = 0.f; adb[c][k] = 0.f; }
   }
   const float inv_n = 1.0f / static_cast<float>(cols);
-  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
-    const size_t base = static_cast<size_t>(r) * cols;
-    const float mu = mean[r], rs = rstd[r];
-    float gd[NC][8], xh[NC][8];
-    float s1 = 0.f, s2 = 0.f;
+  for (int r0 = 2 * blockIdx.x; r0 < rows; r0 += 2 * gridDim.x) {
+    const bool two = r0 + 1 < rows;
+    const int rr[2] = {r0, two ? r0 + 1 : r0};
+    float gd[2][NC][8], xh[2][NC][8], dr[2][NC][8];
+    float mu[2], rs[2];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
-      if (j0 < cols) {
-        load8(dy + base + j0, gd[c]);
-        load8(x + base + j0, xh[c]);
+    for (int q = 0; q < 2; ++q) {
+      mu[q] = mean[rr[q]];
+      rs[q] = rstd[rr[q]];
+      const size_t base = static_cast<size_t>(rr[q]) * cols;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          xh[c][k] = (xh[c][k] - mu) * rs;
-          adg[c][k] += gd[c][k] * xh[c][k];
-          adb[c][k] += gd[c][k];
-          gd[c][k] *= g[c][k];
-          s1 += gd[c][k];
-          s2 += gd[c][k] * xh[c][k];
+      for (int c = 0; c < NC; ++c) {
+        const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+        if (j0 < cols) {
+          load8(dy + base + j0, gd[q][c]);
+          load8(x + base + j0, xh[q][c]);
+          load8(dres + base + j0, dr[q][c]);
         }
       }
     }
-    block_sum2(s1, s2, smem);
-    const float m1 = s1 * inv_n, m2 = s2 * inv_n;
+    float sums[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
-      if (j0 < cols) {
-        float o[8];
-        load8(dres + base + j0, o);
+    for (int q = 0; q < 2; ++q) {
+      const float live = (q == 0 || two) ? 1.0f : 0.0f;  // a lone last row is not counted twice
 #pragma unroll
-        for (int k = 0; k < 8; ++k) o[k] += rs * (gd[c][k] - m1 - xh[c][k] * m2);
-        store8(dx_out + base + j0, o);
+      for (int c = 0; c < NC; ++c) {
+        const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+        if (j0 < cols) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            xh[q][c][k] = (xh[q][c][k] - mu[q]) * rs[q];
+            adg[c][k] += live * gd[q][c][k] * xh[q][c][k];
+            adb[c][k] += live * gd[q][c][k];
+            gd[q][c][k] *= g[c][k];
+            sums[2 * q] += gd[q][c][k];
+            sums[2 * q + 1] += gd[q][c][k] * xh[q][c][k];
+          }
+        }
+      }
+    }
+    block_sum4(sums, smem);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      if (q == 1 && !two) break;
+      const size_t base = static_cast<size_t>(rr[q]) * cols;
+      const float m1 = sums[2 * q] * inv_n, m2 = sums[2 * q + 1] * inv_n;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
+        if (j0 < cols) {
+          float o[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k)
+            o[k] = dr[q][c][k] + rs[q] * (gd[q][c][k] - m1 - xh[q][c][k] * m2);
+          store8(dx_out + base + j0, o);
+        }
       }
     }
   }
@@ -145,7 +173,10 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
   }
 }
 
-int bwd_blocks(int rows) { return rows < kBwdMaxBlocks ? rows : kBwdMaxBlocks; }
+int bwd_blocks(int rows) {
+  const int pairs = (rows + 1) / 2;
+  return pairs < kBwdMaxBlocks ? pairs : kBwdMaxBlocks;
+}
 
 }  // namespace
 

@@ -65,10 +65,8 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
       for (int k = 0; k < 8; ++k) pr[k] = round_to_storage(z[c][k] * inv, P);
       if (P != nullptr) store8(P + row + j0, pr);
       if (Pd != nullptr) {
-        uint32_t keep = 0;
-        if (j0 < nvalid) keep = dropout_keep8(key, (gidx + j0) >> 3);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) pr[k] = ((keep >> k) & 1u) ? pr[k] * key.scale : 0.0f;
+        // entries beyond the diagonal are exactly 0 already; the zero padding needs no draw
+        if (j0 < nvalid) dropout_apply8(key, (gidx + j0) >> 3, pr);
         store8(Pd + row + j0, pr);
       }
     }
@@ -90,15 +88,13 @@ attn_dropout_fwd_kernel(const T* __restrict__ P, T* __restrict__ Pd, int s, int 
   const int nvalid = i + 1;
   const int npad = min(s, (nvalid + kPad - 1) / kPad * kPad);
   for (int j0 = lane * 8; j0 < npad; j0 += kWave * 8) {
-    float pr[8];
-    uint32_t keep = 0;
+    float pr[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (j0 < nvalid) {
       load8(P + row + j0, pr);
-      keep = dropout_keep8(key, (gidx + j0) >> 3);
-    }
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      pr[k] = (((keep >> k) & 1u) && (j0 + k < nvalid)) ? pr[k] * key.scale : 0.0f;
+      for (int k = 0; k < 8; ++k) pr[k] = (j0 + k < nvalid) ? pr[k] : 0.0f;
+      dropout_apply8(key, (gidx + j0) >> 3, pr);
+    }
     store8(Pd + row + j0, pr);
   }
 }
@@ -126,14 +122,14 @@ softmax_dropout_bwd_kernel(const T* dPd, const T* __restrict__ P, T* dS,  // dS 
     if (j0 < nvalid) {
       load8(dPd + row + j0, dp[c]);
       load8(P + row + j0, p[c]);
-      const uint32_t keep = dropout_keep8(key, (gidx + j0) >> 3);
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const bool on = ((keep >> k) & 1u) && (j0 + k < nvalid);
-        dp[c][k] = on ? dp[c][k] * key.scale : 0.0f;
+      for (int k = 0; k < 8; ++k) {  // beyond the diagonal dPd holds whatever the product left
+        dp[c][k] = (j0 + k < nvalid) ? dp[c][k] : 0.0f;
         p[c][k] = (j0 + k < nvalid) ? p[c][k] : 0.0f;
-        dot += dp[c][k] * p[c][k];
       }
+      dropout_apply8(key, (gidx + j0) >> 3, dp[c]);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) dot += dp[c][k] * p[c][k];
     } else {
 #pragma unroll
       for (int k = 0; k < 8; ++k) { dp[c][k] = 0.f; p[c][k] = 0.f; }

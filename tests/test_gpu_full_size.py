@@ -41,8 +41,11 @@ def test_single_layer_full_size(name):
     cfg = synth.CONFIGS[name]
     params = synth.make_params(cfg)
     X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
-    layer = GpuLayer(cfg, params, workspace_bytes=None, retain_mask_for_size=pm.STORE_ALL)
-    B = layer.B
+    from paper_2406_08756_amd import binding as B
+    policies = [POLICY[name]] if name != "C2" else [pm.ATTENTION_ONLY, pm.FULL_RECOMPUTE]
+    # the workspace size is exact per policy (buffers are placed differently under each)
+    need = max(B.lynx_workspace_bytes(cfg, m) for m in [pm.STORE_ALL] + policies)
+    layer = GpuLayer(cfg, params, workspace_bytes=need)
     # every activation, from a store-all forward
     layer.forward(X, pm.STORE_ALL)
     torch.cuda.synchronize()
@@ -58,7 +61,6 @@ def test_single_layer_full_size(name):
     for k, v in layer.grads.items():
         check(gold, "grad." + k, v)
     # the timed configuration: policy forward, regeneration, backward -- same bits
-    policies = [POLICY[name]] if name != "C2" else [pm.ATTENTION_ONLY, pm.FULL_RECOMPUTE]
     for mask in policies:
         layer.dx.zero_()
         for v in layer.grads.values():
