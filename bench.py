@@ -48,14 +48,13 @@ def slot_work(cfg):
         "op9_layernorm2": ("hbm", 2 * T * h * e), "op10_fc1_gemm": ("mfma", lin(f, h)),
         "op11_gelu": ("hbm", 2 * T * f * e), "op12_fc2_gemm": ("mfma", lin(h, f)),
         "op13_bias_dropout_add2": ("hbm", 3 * T * h * e),
-        "b13_dropout_bwd": ("hbm", 2 * T * h * e), "b12_fc2_dgrad": ("mfma", lin(h, f)),
-        "b12_fc2_wgrad": ("mfma", lin(h, f)), "b11_gelu_bwd": ("hbm", 3 * T * f * e),
-        "b10_fc1_dgrad": ("mfma", lin(f, h)), "b10_fc1_wgrad": ("mfma", lin(f, h)),
+        "b13_dropout_bwd": ("hbm", 2 * T * h * e), "b12_fc2_dgrad_wgrad": ("mfma", 2 * lin(h, f)),
+        "b11_gelu_bwd": ("hbm", 3 * T * f * e), "b10_fc1_dgrad_wgrad": ("mfma", 2 * lin(f, h)),
         "b9_layernorm2_bwd": ("hbm", 4 * T * h * e), "b8_dropout_bwd": ("hbm", 2 * T * h * e),
-        "b7_proj_dgrad": ("mfma", lin(h, p)), "b7_proj_wgrad": ("mfma", lin(h, p)),
+        "b7_proj_dgrad_wgrad": ("mfma", 2 * lin(h, p)),
         "b6_dpd": ("mfma", att), "b6_dv": ("mfma", att), "b54_softmax_dropout_bwd": ("hbm", 3 * tri * e),
-        "b3_dq": ("mfma", att), "b3_dk": ("mfma", att), "b2_qkv_dgrad": ("mfma", lin(3 * p, h)),
-        "b2_qkv_wgrad": ("mfma", lin(3 * p, h)), "b2_bias_grad": ("hbm", T * 3 * p * e),
+        "b3_dq": ("mfma", att), "b3_dk": ("mfma", att), "b2_qkv_dgrad_wgrad": ("mfma", 2 * lin(3 * p, h)),
+        "b2_bias_grad": ("hbm", T * 3 * p * e),
         "b1_layernorm1_bwd": ("hbm", 4 * T * h * e),
     }
 
@@ -215,7 +214,7 @@ def main():
     # dominant kernel: the dense linear-layer products (forward, dgrad, wgrad share
     # one kernel family); quote the one with the most time per step
     dense = [n for n in kernels if kernels[n]["bound"] == "mfma"
-             and ("gemm" in n or n.endswith(("dgrad", "wgrad")))]
+             and ("gemm" in n or n.endswith("dgrad_wgrad"))]
     dom = max(dense, key=lambda n: kernels[n]["ms"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["achieved"], "peak": mfma_peak,
                 "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": None,

@@ -124,8 +124,9 @@ struct Slab {
   }
 };
 
+// One output tile: `block_x` selects the tile, `block_z` the matrix of a batch.
 template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN>
-__global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
+__device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block_x, const int block_z) {
   constexpr int WM = BM / 2, WN = BN / 2;  // wavefronts in a 2 x 2 grid
   constexpr int TM = WM / 32, TN = WN / 32;
   using SA = Slab<BM, A_KMAJOR>;
@@ -139,7 +140,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   int tm, tn;
   if (g.causal == kCausalOutLower) {
     // square output, only tiles on or below the diagonal: t = tm (tm + 1) / 2 + tn
-    const int t = blockIdx.x;
+    const int t = block_x;
     tm = static_cast<int>((sqrtf(8.0f * static_cast<float>(t) + 1.0f) - 1.0f) * 0.5f);
     while (tm * (tm + 1) / 2 > t) --tm;
     while ((tm + 1) * (tm + 2) / 2 <= t) ++tm;
@@ -149,7 +150,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
     // each XCD a contiguous run of tiles, ordered in bands of 8 tile-rows so a band's
     // panels stay in that XCD's L2.
     const int ntiles = g.tiles_m * g.tiles_n;
-    int tile = blockIdx.x;
+    int tile = block_x;
     const int per_xcd = ntiles / 8;
     if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
     constexpr int kBand = 8;
@@ -164,7 +165,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   int k_begin = 0, k_end = g.K;
   if (g.causal == kCausalKLeM) k_end = min(g.K, m0 + BM);
   if (g.causal == kCausalKGeM) k_begin = m0;
-  const int z1 = blockIdx.y / g.nz2, z2 = blockIdx.y - z1 * g.nz2;
+  const int z1 = block_z / g.nz2, z2 = block_z - z1 * g.nz2;
   const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2;
   const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
   bf16_t* Cbase = g.C + z1 * g.c_z1 + z2 * g.c_z2;
@@ -333,6 +334,25 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   }
 }
 
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN>
+__global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
+  gemm_tile<A_KMAJOR, B_KMAJOR, BM, BN>(g, blockIdx.x, blockIdx.y);
+}
+
+// The two products of a linear layer's backward in one launch: the weight gradient
+// (both operands MN-major, long contraction over the tokens) takes the first n_w
+// workgroups, the input gradient (weight MN-major) the rest.  Sharing a launch lets
+// the second product's tiles fill the compute units the first leaves idle in its
+// last, partial round.
+template <int DBM, int DBN, int WBM, int WBN>
+__global__ void __launch_bounds__(kThreads)
+gemm_mfma_pair_kernel(MfmaGemmArgs wgrad, MfmaGemmArgs dgrad, int n_w) {
+  if (static_cast<int>(blockIdx.x) < n_w)
+    gemm_tile<false, false, WBM, WBN>(wgrad, blockIdx.x, 0);
+  else
+    gemm_tile<true, false, DBM, DBN>(dgrad, blockIdx.x - n_w, 0);
+}
+
 template <bool AK, bool BK_, int BM, int BN>
 hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
   constexpr size_t smem = static_cast<size_t>(kStages) * (BM + BN) * kBK * sizeof(bf16_t);
@@ -389,6 +409,48 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
   }
 }
 
+// Largest tile that divides the output (pair launches share their tail, so there is
+// no reason to shrink tiles for occupancy).
+bool pick_tile(const MfmaGemmArgs& a, int* bm, int* bn) {
+  *bm = a.M % 256 == 0 ? 256 : 128;
+  *bn = a.N % 256 == 0 ? 256 : 128;
+  return a.M % *bm == 0 && a.N % *bn == 0;
+}
+
+template <int DBM, int DBN, int WBM, int WBN>
+hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, hipStream_t st) {
+  constexpr int dsum = DBM + DBN, wsum = WBM + WBN;
+  constexpr size_t smem = static_cast<size_t>(kStages) * (dsum > wsum ? dsum : wsum) * kBK * sizeof(bf16_t);
+  auto kern = gemm_mfma_pair_kernel<DBM, DBN, WBM, WBN>;
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(smem));
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  w.tiles_m = w.M / WBM; w.tiles_n = w.N / WBN;
+  d.tiles_m = d.M / DBM; d.tiles_n = d.N / DBN;
+  const int n_w = w.tiles_m * w.tiles_n;
+  hipLaunchKernelGGL(kern, dim3(n_w + d.tiles_m * d.tiles_n), dim3(kThreads), smem, st, w, d, n_w);
+  return hipGetLastError();
+}
+
+MfmaGemmArgs make_args(const GemmDesc& d) {
+  MfmaGemmArgs a{};
+  const bool a_k = d.a_sk == 1, b_k = d.b_sk == 1;
+  a.A = static_cast<const bf16_t*>(d.A); a.lda = a_k ? d.a_sm : d.a_sk;
+  a.B = static_cast<const bf16_t*>(d.B); a.ldb = b_k ? d.b_sn : d.b_sk;
+  a.C = static_cast<bf16_t*>(d.C); a.ldc = d.c_sm;
+  a.bias = static_cast<const bf16_t*>(d.bias);
+  a.M = d.M; a.N = d.N; a.K = d.K;
+  a.a_z1 = d.a_sz1; a.a_z2 = d.a_sz2; a.b_z1 = d.b_sz1; a.b_z2 = d.b_sz2;
+  a.c_z1 = d.c_sz1; a.c_z2 = d.c_sz2;
+  a.nz = d.nz1 * d.nz2; a.nz2 = d.nz2; a.causal = d.causal;
+  return a;
+}
+
 }  // namespace
 
 bool gemm_mfma_supported(int dtype, const GemmDesc& d) {
@@ -408,20 +470,41 @@ bool gemm_mfma_supported(int dtype, const GemmDesc& d) {
 }
 
 hipError_t gemm_mfma(const GemmDesc& d, hipStream_t st) {
-  MfmaGemmArgs a{};
+  const MfmaGemmArgs a = make_args(d);
   const bool a_k = d.a_sk == 1, b_k = d.b_sk == 1;
-  a.A = static_cast<const bf16_t*>(d.A); a.lda = a_k ? d.a_sm : d.a_sk;
-  a.B = static_cast<const bf16_t*>(d.B); a.ldb = b_k ? d.b_sn : d.b_sk;
-  a.C = static_cast<bf16_t*>(d.C); a.ldc = d.c_sm;
-  a.bias = static_cast<const bf16_t*>(d.bias);
-  a.M = d.M; a.N = d.N; a.K = d.K;
-  a.a_z1 = d.a_sz1; a.a_z2 = d.a_sz2; a.b_z1 = d.b_sz1; a.b_z2 = d.b_sz2;
-  a.c_z1 = d.c_sz1; a.c_z2 = d.c_sz2;
-  a.nz = d.nz1 * d.nz2; a.nz2 = d.nz2; a.causal = d.causal;
   if (a_k && b_k) return launch_tiles<true, true>(a, st);
   if (a_k && !b_k) return launch_tiles<true, false>(a, st);
   if (!a_k && b_k) return launch_tiles<false, true>(a, st);
   return launch_tiles<false, false>(a, st);
+}
+
+bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad) {
+  if (!gemm_mfma_supported(dtype, dgrad) || !gemm_mfma_supported(dtype, wgrad)) return false;
+  if (dgrad.nz1 * dgrad.nz2 != 1 || wgrad.nz1 * wgrad.nz2 != 1) return false;
+  if (dgrad.causal != kCausalNone || wgrad.causal != kCausalNone) return false;
+  if (!(dgrad.a_sk == 1 && dgrad.b_sn == 1 && dgrad.b_sk != 1)) return false;  // A K-major, B MN-major
+  if (!(wgrad.a_sm == 1 && wgrad.a_sk != 1 && wgrad.b_sn == 1 && wgrad.b_sk != 1)) return false;
+  int bm, bn;
+  const MfmaGemmArgs d = make_args(dgrad), w = make_args(wgrad);
+  if (!pick_tile(d, &bm, &bn) || bm != 256) return false;
+  if (!pick_tile(w, &bm, &bn) || (bm == 128 && bn == 128)) return false;
+  return true;
+}
+
+hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st) {
+  const MfmaGemmArgs d = make_args(dgrad), w = make_args(wgrad);
+  int dbm, dbn, wbm, wbn;
+  pick_tile(d, &dbm, &dbn);
+  pick_tile(w, &wbm, &wbn);
+  const int wsel = wbm == 256 ? (wbn == 256 ? 0 : 1) : 2;
+  if (dbn == 256) {
+    if (wsel == 0) return launch_pair<256, 256, 256, 256>(w, d, st);
+    if (wsel == 1) return launch_pair<256, 256, 256, 128>(w, d, st);
+    return launch_pair<256, 256, 128, 256>(w, d, st);
+  }
+  if (wsel == 0) return launch_pair<256, 128, 256, 256>(w, d, st);
+  if (wsel == 1) return launch_pair<256, 128, 256, 128>(w, d, st);
+  return launch_pair<256, 128, 128, 256>(w, d, st);
 }
 
 }  // namespace lynx

@@ -91,5 +91,10 @@ hipError_t gemm(int dtype, const GemmDesc& d, hipStream_t st);          // picks
 hipError_t gemm_generic(int dtype, const GemmDesc& d, hipStream_t st);  // any shape, vector ALUs
 bool gemm_mfma_supported(int dtype, const GemmDesc& d);                  // bf16, tile-aligned, unbatched
 hipError_t gemm_mfma(const GemmDesc& d, hipStream_t st);                // matrix cores
+// Input gradient and weight gradient of one linear layer, in one launch when the
+// matrix-core kernel can pair them, else one after the other.
+hipError_t gemm_pair(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st);
+bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad);
+hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st);
 
 }  // namespace lynx

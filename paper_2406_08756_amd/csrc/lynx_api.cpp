@@ -141,18 +141,17 @@ struct Ctx {  // one pass (rehearsal or real) of a call
 
 // profile slots: 1..13 = forward operators; then the backward kernels in order
 enum BackwardSlot {
-  kB13Dropout = 14, kB12Dgrad, kB12Wgrad, kB11Gelu, kB10Dgrad, kB10Wgrad, kB9LayerNorm,
-  kB8Dropout, kB7Dgrad, kB7Wgrad, kB6DPd, kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Dgrad, kB2Wgrad,
-  kB2BiasGrad, kB1LayerNorm, kNumSlots
+  kB13Dropout = 14, kB12Grads, kB11Gelu, kB10Grads, kB9LayerNorm, kB8Dropout, kB7Grads, kB6DPd,
+  kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kNumSlots
 };
 static_assert(kNumSlots <= LYNX_PROFILE_SLOTS, "profile slots");
 const char* const kSlotNames[kNumSlots] = {
     "", "op1_layernorm1", "op2_qkv_gemm", "op3_scores", "op4_softmax_dropout", "op5_attn_dropout",
     "op6_context", "op7_attn_proj_gemm", "op8_bias_dropout_add1", "op9_layernorm2", "op10_fc1_gemm",
-    "op11_gelu", "op12_fc2_gemm", "op13_bias_dropout_add2", "b13_dropout_bwd", "b12_fc2_dgrad",
-    "b12_fc2_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad", "b10_fc1_wgrad", "b9_layernorm2_bwd",
-    "b8_dropout_bwd", "b7_proj_dgrad", "b7_proj_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd",
-    "b3_dq", "b3_dk", "b2_qkv_dgrad", "b2_qkv_wgrad", "b2_bias_grad", "b1_layernorm1_bwd"};
+    "op11_gelu", "op12_fc2_gemm", "op13_bias_dropout_add2", "b13_dropout_bwd",
+    "b12_fc2_dgrad_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad_wgrad", "b9_layernorm2_bwd",
+    "b8_dropout_bwd", "b7_proj_dgrad_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd", "b3_dq",
+    "b3_dk", "b2_qkv_dgrad_wgrad", "b2_bias_grad", "b1_layernorm1_bwd"};
 
 char* act_ptr(const Ctx& cx, int i) {
   if (i == 0) return const_cast<char*>(static_cast<const char*>(cx.L->x));
@@ -467,10 +466,8 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
                                     dropout_params(L), cx.st));
   // B12: V2 = G W2^T
   LYNX_TRY(alloc_temp(cx, tf, &t_dg));
-  LYNX_LAUNCH(cx, kB12Dgrad, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T,
-                                              D.h, D.f), cx.st));
-  LYNX_LAUNCH(cx, kB12Wgrad, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T,
-                                              D.h, D.f), cx.st));
+  LYNX_LAUNCH(cx, kB12Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T, D.h, D.f),
+                                                  linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T, D.h, D.f), cx.st));
   free_temp(cx, &t_dv2);
   free_act(cx, 11);
   // B11: G = gelu(U)
@@ -481,10 +478,8 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   free_act(cx, 10);
   // B10: U = Y2 W1^T + b1
   LYNX_TRY(alloc_temp(cx, th, &t_dy2));
-  LYNX_LAUNCH(cx, kB10Dgrad, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T,
-                                              D.f, D.h), cx.st));
-  LYNX_LAUNCH(cx, kB10Wgrad, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f,
-                                              D.h), cx.st));
+  LYNX_LAUNCH(cx, kB10Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T, D.f, D.h),
+                                                  linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f, D.h), cx.st));
   free_temp(cx, &t_du);
   // B9: Y2 = LN2(X2); dX2 = dOUT + dLN
   LYNX_TRY(alloc_temp(cx, th, &t_dx2));
@@ -500,10 +495,8 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
                                     D.h, 1, dropout_params(L), cx.st));
   // B7: O = C Wo^T
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * D.p * e, &t_dc));
-  LYNX_LAUNCH(cx, kB7Dgrad, lynx::gemm(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T,
-                                              D.h, D.p), cx.st));
-  LYNX_LAUNCH(cx, kB7Wgrad, lynx::gemm(dt, linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h,
-                                              D.p), cx.st));
+  LYNX_LAUNCH(cx, kB7Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T, D.h, D.p),
+                                                  linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h, D.p), cx.st));
   free_temp(cx, &t_do);
   free_act(cx, 6);
   // B6: C = Pd V
@@ -535,10 +528,8 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   free_act(cx, 3);
   // B2: QKV = Y1 Wqkv^T + bqkv
   LYNX_TRY(alloc_temp(cx, th, &t_dy1));
-  LYNX_LAUNCH(cx, kB2Dgrad, lynx::gemm(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
-                             cx.st));
-  LYNX_LAUNCH(cx, kB2Wgrad, lynx::gemm(dt, linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h),
-                             cx.st));
+  LYNX_LAUNCH(cx, kB2Grads, lynx::gemm_pair(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
+                                                  linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h), cx.st));
   LYNX_LAUNCH(cx, kB2BiasGrad, lynx::column_sum(dt, dqkv, gr->bqkv, scr, D.T, 3 * D.p, cx.st));
   free_temp(cx, &t_dqkv);
   free_act(cx, 2);
