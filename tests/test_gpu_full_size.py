@@ -1,9 +1,15 @@
 """GPU parity at the full workload shapes (C2..C5), in the launch configuration
 bench.py times: sampled entries of every tensor against values the fp64 oracle
 computed on the same seeded inputs (tests/golden/full_size_*.npz, written by
-tests/golden/make_full_size_samples.py, which calls only the oracle).  Bound:
-|gpu - ref| <= 2e-2 * max|ref| per tensor (bf16 storage).  Also: results are
-bit-identical across retain policies at full size."""
+tests/golden/make_full_size_samples.py, which calls only the oracle).  Bound for
+one layer: |gpu - ref| <= 2e-2 * max|ref| per tensor (bf16 storage).  Also:
+results are bit-identical across retain policies at full size.
+
+In the six-layer slice every layer boundary tensor (OUT going up, dX coming
+down) is stored in bf16, so the independent rounding errors of successive
+layers add in quadrature: a gradient that has come down through k layer
+backward passes is held to 2e-2 * sqrt(k), the per-layer bar for k = 1.  The
+forward outputs OUT are held to the plain 2e-2 at every depth."""
 import os
 
 import numpy as np
@@ -27,11 +33,11 @@ def load(name):
     return np.load(path)
 
 
-def check(gold, key, flat_gpu):
+def check(gold, key, flat_gpu, tol=TOL):
     idx = torch.from_numpy(gold[key + ".idx"]).cuda()
     got = flat_gpu.reshape(-1)[idx].float().cpu().numpy().astype(np.float64)
     err = np.abs(got - gold[key + ".val"]).max() / max(float(gold[key + ".max"]), 1e-30)
-    assert err <= TOL, (key, err)
+    assert err <= tol, (key, err, tol)
     return err
 
 
@@ -95,8 +101,9 @@ def test_six_layer_slice_full_size():
         layers[l].backward(g if l == L - 1 else layers[l + 1].dx)
     torch.cuda.synchronize()
     for l in range(L):
-        check(gold, "L%d.grad.dX" % l, layers[l].dx)
+        tol = TOL * np.sqrt(L - l)  # backward passes between the injected dOUT and this layer's gradients
+        check(gold, "L%d.grad.dX" % l, layers[l].dx, tol)
         for k, v in layers[l].grads.items():
-            check(gold, "L%d.grad.%s" % (l, k), v)
+            check(gold, "L%d.grad.%s" % (l, k), v, tol)
     for lay in layers:
         lay.close()
