@@ -24,6 +24,15 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch (L2 misses + write-backs) of the dense GEMM groups, from the two
+# hardware-counter runs summarised in profiles/bench_C4_full_recompute_hbm_traffic.md
+# (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Not measured live:
+# counters need the profiler around the process.
+MEASURED_TRAFFIC_BYTES = {("C4", "full"): {
+    "b12_fc2_dgrad_wgrad": 2297.9e6, "b10_fc1_dgrad_wgrad": 2170.0e6, "b2_qkv_dgrad_wgrad": 2205.8e6,
+    "b7_proj_dgrad_wgrad": 1222.3e6, "op10_fc1_gemm": 797.2e6, "op12_fc2_gemm": 797.2e6,
+    "op2_qkv_gemm": 891.4e6, "op7_attn_proj_gemm": 325.4e6}}
+
 POLICIES = {"store_all": 0x3FFF, "full": 0x2001, "attention_only": 0x3FFF & ~0x0038,
             "elementwise_only": 0x3FFF & ~0x0830}
 
@@ -119,6 +128,9 @@ def main():
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--policy", default=None, choices=list(POLICIES))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (the known-size kernel that "
+                         "hardware-counter runs of this command are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -160,6 +172,10 @@ def main():
         B.lynx_layer_backward(layer, dout, dx, grads, stream)
         if ev: ev[3].record(stream)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        torch.empty_like(src).copy_(src)
+        del src
     for k in range(args.warmup):
         step(None, k)
     torch.cuda.synchronize()
@@ -216,8 +232,10 @@ def main():
     dense = [n for n in kernels if kernels[n]["bound"] == "mfma"
              and ("gemm" in n or n.endswith("dgrad_wgrad"))]
     dom = max(dense, key=lambda n: kernels[n]["ms"])
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.config, policy), {}).get(dom.split("/")[-1])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["achieved"], "peak": mfma_peak,
-                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": None,
+                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": traffic,
+                "traffic_unit": "bytes per launch (counter runs under profiles/, not live)",
                 "ms_per_launch": kernels[dom]["ms"]}
 
     fwd_f, rec_f, bwd_f = phase_flops(cfg, mask)
