@@ -8,8 +8,10 @@ hipError_t gemm(int dtype, const GemmDesc& d, hipStream_t st) {
   return gemm_generic(dtype, d, st);
 }
 
-hipError_t gemm_pair(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st) {
-  if (gemm_mfma_pair_supported(dtype, dgrad, wgrad)) return gemm_mfma_pair(dgrad, wgrad, st);
+hipError_t gemm_pair(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad, float* scratch,
+                     size_t scratch_bytes, hipStream_t st) {
+  if (gemm_mfma_pair_supported(dtype, dgrad, wgrad))
+    return gemm_mfma_pair(dgrad, wgrad, scratch, scratch_bytes, st);
   const hipError_t e = gemm(dtype, dgrad, st);
   if (e != hipSuccess) return e;
   return gemm(dtype, wgrad, st);

@@ -51,6 +51,10 @@ struct MfmaGemmArgs {
   long long a_z1, a_z2, b_z1, b_z2, c_z1, c_z2;
   int nz, nz2;
   int causal;  // CausalMode
+  // split contraction: workgroup x computes K range x / (tiles_m tiles_n) of k_splits equal
+  // ranges and leaves its fp32 sums in partial[split][M][N] instead of rounding into C
+  int k_splits;
+  float* partial;
 };
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -125,7 +129,7 @@ struct Slab {
 };
 
 // One output tile: `block_x` selects the tile, `block_z` the matrix of a batch.
-template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN>
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, bool SPLITK = false>
 __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block_x, const int block_z) {
   constexpr int WM = BM / 2, WN = BN / 2;  // wavefronts in a 2 x 2 grid
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -151,6 +155,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
     // panels stay in that XCD's L2.
     const int ntiles = g.tiles_m * g.tiles_n;
     int tile = block_x;
+    if (SPLITK) tile = block_x % ntiles;
     const int per_xcd = ntiles / 8;
     if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
     constexpr int kBand = 8;
@@ -165,6 +170,11 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
   int k_begin = 0, k_end = g.K;
   if (g.causal == kCausalKLeM) k_end = min(g.K, m0 + BM);
   if (g.causal == kCausalKGeM) k_begin = m0;
+  const int split = SPLITK ? block_x / (g.tiles_m * g.tiles_n) : 0;
+  if (SPLITK) {
+    k_begin = split * (g.K / g.k_splits);
+    k_end = k_begin + g.K / g.k_splits;
+  }
   const int z1 = block_z / g.nz2, z2 = block_z - z1 * g.nz2;
   const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2;
   const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
@@ -300,6 +310,22 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
   // its own region of the now idle LDS ring and writes it out as whole rows, 16 bytes per
   // lane.  16-byte chunks of LDS row r are XORed with r so both the 8-byte writes and the
   // 16-byte row reads spread over all banks.
+  if (SPLITK) {
+    // partial sums of one K range: fp32, four consecutive n per lane
+    float* pw = g.partial + (static_cast<long long>(split) * g.M + m0 + wm0 + (lane & 31)) * g.N + n0 + wn0 +
+                4 * (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float4 v = {acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                            acc[i][j][4 * q + 3]};
+          *reinterpret_cast<float4*>(pw + static_cast<long long>(32 * j) * g.N + 32 * i + 8 * q) = v;
+        }
+    return;
+  }
   block_barrier();  // every wavefront is done with the ring (no load is in flight any more)
   constexpr int kRowChunks = WN / 8;
   bf16_t* stage = smem + wave * (WM * WN);
@@ -347,10 +373,33 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
 template <int DBM, int DBN, int WBM, int WBN>
 __global__ void __launch_bounds__(kThreads)
 gemm_mfma_pair_kernel(MfmaGemmArgs wgrad, MfmaGemmArgs dgrad, int n_w) {
-  if (static_cast<int>(blockIdx.x) < n_w)
-    gemm_tile<false, false, WBM, WBN>(wgrad, blockIdx.x, 0);
-  else
+  if (static_cast<int>(blockIdx.x) < n_w) {
+    if (wgrad.k_splits > 1) gemm_tile<false, false, WBM, WBN, true>(wgrad, blockIdx.x, 0);
+    else gemm_tile<false, false, WBM, WBN>(wgrad, blockIdx.x, 0);
+  } else
     gemm_tile<true, false, DBM, DBN>(dgrad, blockIdx.x - n_w, 0);
+}
+
+// C[m][n] = round(sum over the K ranges, in range order, of partial[split][m][n]).
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C, int M, int N, long long ldc,
+                     int k_splits) {
+  const long long v = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;  // 8 consecutive n
+  const int per_row = N / 8;
+  if (v >= static_cast<long long>(M) * per_row) return;
+  const int m = static_cast<int>(v / per_row), n = static_cast<int>(v - static_cast<long long>(m) * per_row) * 8;
+  const float* p = partial + static_cast<long long>(m) * N + n;
+  float4 lo = *reinterpret_cast<const float4*>(p), hi = *reinterpret_cast<const float4*>(p + 4);
+  for (int sp = 1; sp < k_splits; ++sp) {
+    p += static_cast<long long>(M) * N;
+    const float4 l2 = *reinterpret_cast<const float4*>(p), h2 = *reinterpret_cast<const float4*>(p + 4);
+    lo.x += l2.x; lo.y += l2.y; lo.z += l2.z; lo.w += l2.w;
+    hi.x += h2.x; hi.y += h2.y; hi.z += h2.z; hi.w += h2.w;
+  }
+  uint4 o;
+  o.x = pack_bf16(lo.x, lo.y); o.y = pack_bf16(lo.z, lo.w);
+  o.z = pack_bf16(hi.x, hi.y); o.w = pack_bf16(hi.z, hi.w);
+  *reinterpret_cast<uint4*>(C + static_cast<long long>(m) * ldc + n) = o;
 }
 
 template <bool AK, bool BK_, int BM, int BN>
@@ -432,9 +481,34 @@ hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, hipStream_t st) {
   }
   w.tiles_m = w.M / WBM; w.tiles_n = w.N / WBN;
   d.tiles_m = d.M / DBM; d.tiles_n = d.N / DBN;
-  const int n_w = w.tiles_m * w.tiles_n;
+  const int n_w = w.tiles_m * w.tiles_n * w.k_splits;
   hipLaunchKernelGGL(kern, dim3(n_w + d.tiles_m * d.tiles_n), dim3(kThreads), smem, st, w, d, n_w);
+  if (w.k_splits > 1) {
+    const long long vecs = static_cast<long long>(w.M) * (w.N / 8);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>((vecs + 255) / 256)), dim3(256), 0, st,
+                       w.partial, w.C, w.M, w.N, w.ldc, w.k_splits);
+  }
   return hipGetLastError();
+}
+
+// How many K ranges (1 or 2) the weight gradient of a pair is cut into.  Its tiles contract
+// over all tokens and are few; when one of them lasts longer than three quarters of the
+// launch's ideal duration, the compute units that have finished the input gradient wait for
+// it, and halving it pays for the extra pass over the fp32 partial sums (measured: 10-30 %
+// on the attention-projection shapes; finer cuts and cuts of the wide layers lose to that
+// pass).  Durations in slab units: 1 per slab for a 256 x 256 tile, about 0.55 for the
+// narrower ones.
+int pair_k_splits(int wM, int wN, int wK, int dM, int dN, int dK) {
+  auto tiles = [](int M, int N, double* cost) {
+    const int bm = M % 256 == 0 ? 256 : 128, bn = N % 256 == 0 ? 256 : 128;
+    *cost = (bm == 256 && bn == 256) ? 1.0 : 0.55;
+    return static_cast<double>(M / bm) * (N / bn);
+  };
+  double cw, cd;
+  const double nw = tiles(wM, wN, &cw), nd = tiles(dM, dN, &cd);
+  const double ideal = (nw * (wK / kBK) * cw + nd * (dK / kBK) * cd) / 256.0;
+  const bool cut = wK % (2 * kBK) == 0 && wK >= 2048 && (wK / kBK) * cw > 0.75 * ideal;
+  return cut ? 2 : 1;
 }
 
 MfmaGemmArgs make_args(const GemmDesc& d) {
@@ -448,6 +522,7 @@ MfmaGemmArgs make_args(const GemmDesc& d) {
   a.a_z1 = d.a_sz1; a.a_z2 = d.a_sz2; a.b_z1 = d.b_sz1; a.b_z2 = d.b_sz2;
   a.c_z1 = d.c_sz1; a.c_z2 = d.c_sz2;
   a.nz = d.nz1 * d.nz2; a.nz2 = d.nz2; a.causal = d.causal;
+  a.k_splits = 1; a.partial = nullptr;
   return a;
 }
 
@@ -491,8 +566,22 @@ bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& 
   return true;
 }
 
-hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st) {
-  const MfmaGemmArgs d = make_args(dgrad), w = make_args(wgrad);
+size_t gemm_pair_scratch_bytes(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad) {
+  if (dtype != 1) return 0;
+  const int s = pair_k_splits(wgrad.M, wgrad.N, wgrad.K, dgrad.M, dgrad.N, dgrad.K);
+  return s > 1 ? static_cast<size_t>(s) * wgrad.M * wgrad.N * sizeof(float) : 0;
+}
+
+hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, float* scratch, size_t scratch_bytes,
+                          hipStream_t st) {
+  const MfmaGemmArgs d = make_args(dgrad);
+  MfmaGemmArgs w = make_args(wgrad);
+  const int splits = pair_k_splits(w.M, w.N, w.K, d.M, d.N, d.K);
+  if (splits > 1 && scratch != nullptr && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0 &&
+      scratch_bytes >= static_cast<size_t>(splits) * w.M * w.N * sizeof(float)) {
+    w.k_splits = splits;
+    w.partial = scratch;
+  }
   int dbm, dbn, wbm, wbn;
   pick_tile(d, &dbm, &dbn);
   pick_tile(w, &wbm, &wbn);

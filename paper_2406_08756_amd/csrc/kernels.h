@@ -93,8 +93,13 @@ bool gemm_mfma_supported(int dtype, const GemmDesc& d);                  // bf16
 hipError_t gemm_mfma(const GemmDesc& d, hipStream_t st);                // matrix cores
 // Input gradient and weight gradient of one linear layer, in one launch when the
 // matrix-core kernel can pair them, else one after the other.
-hipError_t gemm_pair(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st);
+// `scratch` (fp32, 16-byte aligned, gemm_pair_scratch_bytes or more; may be null) lets the
+// weight gradient be cut into K ranges whose partial sums are added in a fixed order.
+hipError_t gemm_pair(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad, float* scratch,
+                     size_t scratch_bytes, hipStream_t st);
+size_t gemm_pair_scratch_bytes(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad);  // shapes only
 bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad);
-hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, hipStream_t st);
+hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, float* scratch, size_t scratch_bytes,
+                          hipStream_t st);
 
 }  // namespace lynx

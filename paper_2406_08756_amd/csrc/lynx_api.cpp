@@ -455,6 +455,14 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   size_t scratch_bytes = lynx::colsum_scratch_bytes(D.T, widest);
   const size_t ln_bytes = lynx::layernorm_bwd_scratch_bytes(D.T, D.h);
   if (ln_bytes > scratch_bytes) scratch_bytes = ln_bytes;
+  {  // fp32 partial sums of weight gradients that are cut into K ranges
+    const int lin[4][2] = {{D.h, D.f}, {D.f, D.h}, {D.h, D.p}, {3 * D.p, D.h}};  // {outputs, inputs}
+    for (const auto& nk : lin) {
+      const size_t b = lynx::gemm_pair_scratch_bytes(dt, linear_dgrad(nullptr, nullptr, nullptr, D.T, nk[0], nk[1]),
+                                                     linear_wgrad(nullptr, nullptr, nullptr, D.T, nk[0], nk[1]));
+      if (b > scratch_bytes) scratch_bytes = b;
+    }
+  }
   Temp scratch, t_dv2, t_dg, t_du, t_dy2, t_dx2, t_do, t_dc, t_dpd, t_dqkv, t_dy1;
   LYNX_TRY(alloc_temp(cx, scratch_bytes, &scratch));
   float* scr = reinterpret_cast<float*>(temp_ptr(cx, scratch));
@@ -467,7 +475,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   // B12: V2 = G W2^T
   LYNX_TRY(alloc_temp(cx, tf, &t_dg));
   LYNX_LAUNCH(cx, kB12Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T, D.h, D.f),
-                                                  linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T, D.h, D.f), cx.st));
+                                                  linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T, D.h, D.f), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_dv2);
   free_act(cx, 11);
   // B11: G = gelu(U)
@@ -479,7 +487,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   // B10: U = Y2 W1^T + b1
   LYNX_TRY(alloc_temp(cx, th, &t_dy2));
   LYNX_LAUNCH(cx, kB10Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T, D.f, D.h),
-                                                  linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f, D.h), cx.st));
+                                                  linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f, D.h), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_du);
   // B9: Y2 = LN2(X2); dX2 = dOUT + dLN
   LYNX_TRY(alloc_temp(cx, th, &t_dx2));
@@ -496,7 +504,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   // B7: O = C Wo^T
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * D.p * e, &t_dc));
   LYNX_LAUNCH(cx, kB7Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T, D.h, D.p),
-                                                  linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h, D.p), cx.st));
+                                                  linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h, D.p), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_do);
   free_act(cx, 6);
   // B6: C = Pd V
@@ -529,7 +537,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   // B2: QKV = Y1 Wqkv^T + bqkv
   LYNX_TRY(alloc_temp(cx, th, &t_dy1));
   LYNX_LAUNCH(cx, kB2Grads, lynx::gemm_pair(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
-                                                  linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h), cx.st));
+                                                  linear_wgrad(dqkv, act_ptr(cx, 1), gr->wqkv, D.T, 3 * D.p, D.h), scr, scratch_bytes, cx.st));
   LYNX_LAUNCH(cx, kB2BiasGrad, lynx::column_sum(dt, dqkv, gr->bqkv, scr, D.T, 3 * D.p, cx.st));
   free_temp(cx, &t_dqkv);
   free_act(cx, 2);
