@@ -141,8 +141,18 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
   // workgroup -> output tile
-  int tm, tn;
-  if (g.causal == kCausalOutLower) {
+  int tm, tn, bz = block_z;
+  if (g.causal == kCausalKLeM || g.causal == kCausalKGeM) {
+    // One-dimensional grid over (tile, matrix), longest contraction first: tile row tm
+    // contracts over tm + 1 (k <= m) or tiles_m - tm (k >= m) row blocks, and a launch
+    // that ends on the long tiles leaves most compute units idle meanwhile.  Matrix z
+    // stays on XCD z % 8, whose L2 then keeps its small operand.
+    const int t = block_x / g.nz;
+    bz = block_x - t * g.nz;
+    const int row = t / g.tiles_n;
+    tn = t - row * g.tiles_n;
+    tm = g.causal == kCausalKLeM ? g.tiles_m - 1 - row : row;
+  } else if (g.causal == kCausalOutLower) {
     // square output, only tiles on or below the diagonal: t = tm (tm + 1) / 2 + tn
     const int t = block_x;
     tm = static_cast<int>((sqrtf(8.0f * static_cast<float>(t) + 1.0f) - 1.0f) * 0.5f);
@@ -175,7 +185,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
     k_begin = split * (g.K / g.k_splits);
     k_end = k_begin + g.K / g.k_splits;
   }
-  const int z1 = block_z / g.nz2, z2 = block_z - z1 * g.nz2;
+  const int z1 = bz / g.nz2, z2 = bz - z1 * g.nz2;
   const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2;
   const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
   bf16_t* Cbase = g.C + z1 * g.c_z1 + z2 * g.c_z2;
@@ -415,7 +425,8 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
     configured = true;
   }
   const int ntiles = a.causal == kCausalOutLower ? a.tiles_m * (a.tiles_m + 1) / 2 : a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL(kern, dim3(ntiles, a.nz), dim3(kThreads), smem, st, a);
+  const bool flat = a.causal == kCausalKLeM || a.causal == kCausalKGeM;  // (tile, matrix) in x
+  hipLaunchKernelGGL(kern, flat ? dim3(ntiles * a.nz) : dim3(ntiles, a.nz), dim3(kThreads), smem, st, a);
   return hipGetLastError();
 }
 
@@ -425,13 +436,10 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
 template <bool AK, bool BK_>
 hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
   if (a.causal != kCausalNone) {
-    // attention products: memory-bound, and the zero padding of the seq x seq operands
-    // reaches the next multiple of 128 only, so contraction-restricted products use
-    // 128-row tiles; the score-shaped ones take the largest square tile
-    if (a.causal == kCausalOutLower && a.M % 256 == 0) {
-      a.tiles_m = a.tiles_n = a.M / 256;
-      return launch<AK, BK_, 256, 256>(a, st);
-    }
+    // attention products: memory-bound.  128 x 128 tiles: the zero padding of the
+    // seq x seq operands reaches the next multiple of 128 only, two workgroups fit a
+    // compute unit (one loads while the other stores), and the score-shaped products
+    // write less beyond the diagonal
     a.tiles_m = a.M / 128;
     a.tiles_n = a.N / 128;
     return launch<AK, BK_, 128, 128>(a, st);
