@@ -48,6 +48,34 @@ __device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
   r.z = pack_bf16(v[4], v[5]); r.w = pack_bf16(v[6], v[7]);
   *reinterpret_cast<uint4*>(p) = r;
 }
+
+// 8 storage elements as loaded, before conversion (keeps loads cheap to batch).
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> { uint4 v; };
+template <> struct Raw8<float> { float4 lo, hi; };
+__device__ __forceinline__ void load_raw(const bf16_t* p, Raw8<bf16_t>& r) {
+  r.v = *reinterpret_cast<const uint4*>(p);
+}
+__device__ __forceinline__ void load_raw(const float* p, Raw8<float>& r) {
+  r.lo = *reinterpret_cast<const float4*>(p);
+  r.hi = *reinterpret_cast<const float4*>(p + 4);
+}
+__device__ __forceinline__ void unpack(const Raw8<bf16_t>& r, float (&v)[8]) {
+  v[0] = bf16_lo(r.v.x); v[1] = bf16_hi(r.v.x); v[2] = bf16_lo(r.v.y); v[3] = bf16_hi(r.v.y);
+  v[4] = bf16_lo(r.v.z); v[5] = bf16_hi(r.v.z); v[6] = bf16_lo(r.v.w); v[7] = bf16_hi(r.v.w);
+}
+__device__ __forceinline__ void unpack(const Raw8<float>& r, float (&v)[8]) {
+  v[0] = r.lo.x; v[1] = r.lo.y; v[2] = r.lo.z; v[3] = r.lo.w;
+  v[4] = r.hi.x; v[5] = r.hi.y; v[6] = r.hi.z; v[7] = r.hi.w;
+}
+
+// Makes the compiler forget what it derived from r, so values unpacked from it earlier are
+// recomputed from the (smaller) storage form instead of being kept in registers.
+__device__ __forceinline__ void forget(Raw8<bf16_t>& r) {
+  asm volatile("" : "+v"(r.v.x), "+v"(r.v.y), "+v"(r.v.z), "+v"(r.v.w));
+}
+__device__ __forceinline__ void forget(Raw8<float>&) {}
+
 __device__ __forceinline__ float load1(const float* p) { return *p; }
 __device__ __forceinline__ float load1(const bf16_t* p) {
   return __uint_as_float(static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(p)) << 16);

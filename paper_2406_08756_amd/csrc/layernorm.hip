@@ -1,6 +1,6 @@
-// LayerNorm forward (operators 1 and 9) and backward.  Forward: one wavefront
-// per token row, the row held in registers, two-pass mean / variance in fp32,
-// statistics written for backward.  Backward: one workgroup of four
+// LayerNorm forward (operators 1 and 9) and backward.  Forward: one workgroup
+// per token row, the row held in registers (a few 16-byte vectors per thread),
+// two-pass mean / variance in fp32, statistics written for backward.  Backward: one workgroup of four
 // wavefronts per row stream; each lane owns fixed columns so the per-column
 // sums for dgamma / dbeta accumulate in registers over the rows the workgroup
 // visits, and are then reduced over workgroups in a second fixed-order stage.
@@ -11,24 +11,41 @@
 namespace lynx {
 namespace {
 
-constexpr int kFwdRowsPerBlock = 4;
 constexpr int kBwdThreads = 256;
 constexpr int kBwdMaxBlocks = 1024;
 
-template <typename T, int NC>
-__global__ void __launch_bounds__(kFwdRowsPerBlock* kWave)
+// Sum over the BS threads of a workgroup, every thread gets the total; `slot` is this
+// call's own LDS row, so two calls need no barrier between them.  Fixed combination order.
+template <int BS>
+__device__ __forceinline__ float block_sum(float v, float* slot) {
+  v = wave_sum(v);
+  if (BS == kWave) return v;
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = slot[0];
+#pragma unroll
+  for (int w = 1; w < BS / kWave; ++w) t += slot[w];
+  return t;
+}
+
+// One workgroup of BS threads per row, NC 16-byte vectors per thread: few loads per
+// thread and many rows in flight stream from HBM markedly faster than a whole row per
+// wavefront.  Workgroup b takes row (b % 8) (rows / 8) + b / 8, so that each XCD (which
+// receives every eighth workgroup) walks its own contiguous eighth of the tensor.
+template <typename T, int BS, int NC>
+__global__ void __launch_bounds__(BS)
 layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                      const T* __restrict__ beta, T* __restrict__ y, float* __restrict__ mean,
                      float* __restrict__ rstd, int rows, int cols, float eps) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int r = blockIdx.x * kFwdRowsPerBlock + (threadIdx.x >> 6);
-  if (r >= rows) return;
+  __shared__ float red[2][BS / kWave];
+  int r = blockIdx.x;
+  if ((rows & 7) == 0) r = (r & 7) * (rows >> 3) + (r >> 3);
   const size_t base = static_cast<size_t>(r) * cols;
   float v[NC][8];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int j0 = (lane + c * kWave) * 8;
+    const int j0 = (threadIdx.x + c * BS) * 8;
     if (j0 < cols) {
       load8(x + base + j0, v[c]);
 #pragma unroll
@@ -36,11 +53,11 @@ layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
     }
   }
   const float inv_n = 1.0f / static_cast<float>(cols);
-  const float mu = wave_sum(sum) * inv_n;
+  const float mu = block_sum<BS>(sum, red[0]) * inv_n;
   float sq = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int j0 = (lane + c * kWave) * 8;
+    const int j0 = (threadIdx.x + c * BS) * 8;
     if (j0 < cols) {
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
@@ -49,10 +66,10 @@ layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
       }
     }
   }
-  const float rs = rsqrtf(wave_sum(sq) * inv_n + eps);
+  const float rs = rsqrtf(block_sum<BS>(sq, red[1]) * inv_n + eps);
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int j0 = (lane + c * kWave) * 8;
+    const int j0 = (threadIdx.x + c * BS) * 8;
     if (j0 < cols) {
       float g[8], b[8];
       load8(gamma + j0, g);
@@ -62,7 +79,7 @@ layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
       store8(y + base + j0, v[c]);
     }
   }
-  if (lane == 0) {
+  if (threadIdx.x == 0) {
     mean[r] = mu;
     rstd[r] = rs;
   }
@@ -85,32 +102,34 @@ __device__ __forceinline__ void block_sum4(float (&v)[4], float* smem) {
     v[i] = (smem[4 * i] + smem[4 * i + 1]) + (smem[4 * i + 2] + smem[4 * i + 3]);
 }
 
-// Two rows per iteration: all loads of both rows (dy, x, residual gradient) are
-// issued before the reductions, which doubles the bytes in flight per workgroup
-// and halves the number of workgroup barriers per row.
-template <typename T, int NC>
+// RPI rows per iteration: all loads of those rows (dy, x, residual gradient) are issued
+// before the reductions.  Loaded vectors stay in storage format (half the registers for
+// bf16) and are unpacked where used, once for the sums and once for the output, which
+// buys the occupancy that hides the load latency.
+template <typename T, int NC, int RPI>
 __global__ void __launch_bounds__(kBwdThreads)
 layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                      const float* __restrict__ mean, const float* __restrict__ rstd,
                      const T* __restrict__ gamma, const T* dres, T* dx_out,
                      float* __restrict__ part_dg, float* __restrict__ part_db, int rows, int cols) {
   __shared__ float smem[16];
-  float g[NC][8], adg[NC][8], adb[NC][8];
+  Raw8<T> graw[NC];
+  float adg[NC][8], adb[NC][8];
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
     const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
-    if (j0 < cols) load8(gamma + j0, g[c]);
+    if (j0 < cols) load_raw(gamma + j0, graw[c]);
 #pragma unroll
     for (int k = 0; k < 8; ++k) { adg[c][k] = 0.f; adb[c][k] = 0.f; }
   }
   const float inv_n = 1.0f / static_cast<float>(cols);
-  for (int r0 = 2 * blockIdx.x; r0 < rows; r0 += 2 * gridDim.x) {
-    const bool two = r0 + 1 < rows;
-    const int rr[2] = {r0, two ? r0 + 1 : r0};
-    float gd[2][NC][8], xh[2][NC][8], dr[2][NC][8];
-    float mu[2], rs[2];
+  for (int r0 = RPI * blockIdx.x; r0 < rows; r0 += RPI * gridDim.x) {
+    int rr[RPI];
+    float mu[RPI], rs[RPI];
+    Raw8<T> rdy[RPI][NC], rx[RPI][NC], rdr[RPI][NC];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < RPI; ++q) {
+      rr[q] = r0 + q < rows ? r0 + q : r0;  // a missing row re-reads the first, uncounted
       mu[q] = mean[rr[q]];
       rs[q] = rstd[rr[q]];
       const size_t base = static_cast<size_t>(rr[q]) * cols;
@@ -118,46 +137,63 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
       for (int c = 0; c < NC; ++c) {
         const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
         if (j0 < cols) {
-          load8(dy + base + j0, gd[q][c]);
-          load8(x + base + j0, xh[q][c]);
-          load8(dres + base + j0, dr[q][c]);
+          load_raw(dy + base + j0, rdy[q][c]);
+          load_raw(x + base + j0, rx[q][c]);
+          load_raw(dres + base + j0, rdr[q][c]);
         }
       }
     }
     float sums[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const float live = (q == 0 || two) ? 1.0f : 0.0f;  // a lone last row is not counted twice
+    for (int q = 0; q < RPI; ++q) {
+      const float live = r0 + q < rows ? 1.0f : 0.0f;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
         if (j0 < cols) {
+          float gd[8], xh[8], g[8];
+          unpack(rdy[q][c], gd);
+          unpack(rx[q][c], xh);
+          unpack(graw[c], g);
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
-            xh[q][c][k] = (xh[q][c][k] - mu[q]) * rs[q];
-            adg[c][k] += live * gd[q][c][k] * xh[q][c][k];
-            adb[c][k] += live * gd[q][c][k];
-            gd[q][c][k] *= g[c][k];
-            sums[2 * q] += gd[q][c][k];
-            sums[2 * q + 1] += gd[q][c][k] * xh[q][c][k];
+            xh[k] = (xh[k] - mu[q]) * rs[q];
+            adg[c][k] += live * gd[k] * xh[k];
+            adb[c][k] += live * gd[k];
+            gd[k] *= g[k];
+            sums[2 * q] += gd[k];
+            sums[2 * q + 1] += gd[k] * xh[k];
           }
         }
       }
     }
     block_sum4(sums, smem);
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      if (q == 1 && !two) break;
+    for (int q = 0; q < RPI; ++q)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        forget(rdy[q][c]);
+        forget(rx[q][c]);
+      }
+#pragma unroll
+    for (int q = 0; q < RPI; ++q) {
+      if (r0 + q >= rows) break;
       const size_t base = static_cast<size_t>(rr[q]) * cols;
       const float m1 = sums[2 * q] * inv_n, m2 = sums[2 * q + 1] * inv_n;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
         if (j0 < cols) {
-          float o[8];
+          float gd[8], xh[8], g[8], dr[8], o[8];
+          unpack(rdy[q][c], gd);
+          unpack(rx[q][c], xh);
+          unpack(graw[c], g);
+          unpack(rdr[q][c], dr);
 #pragma unroll
-          for (int k = 0; k < 8; ++k)
-            o[k] = dr[q][c][k] + rs[q] * (gd[q][c][k] - m1 - xh[q][c][k] * m2);
+          for (int k = 0; k < 8; ++k) {
+            xh[k] = (xh[k] - mu[q]) * rs[q];
+            o[k] = dr[k] + rs[q] * (gd[k] * g[k] - m1 - xh[k] * m2);
+          }
           store8(dx_out + base + j0, o);
         }
       }
@@ -173,38 +209,37 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
   }
 }
 
+constexpr int kBwdRowsPerIter = 2;
+
 int bwd_blocks(int rows) {
-  const int pairs = (rows + 1) / 2;
-  return pairs < kBwdMaxBlocks ? pairs : kBwdMaxBlocks;
+  const int groups = (rows + kBwdRowsPerIter - 1) / kBwdRowsPerIter;
+  return groups < kBwdMaxBlocks ? groups : kBwdMaxBlocks;
 }
 
 }  // namespace
 
 hipError_t layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
                          float* mean, float* rstd, int rows, int cols, float eps, hipStream_t st) {
-  if (cols > 8192 || cols % 8) return hipErrorInvalidValue;
-  const dim3 grid((rows + kFwdRowsPerBlock - 1) / kFwdRowsPerBlock);
-  const dim3 block(kFwdRowsPerBlock * kWave);
-  const int nc = (cols / 8 + kWave - 1) / kWave;
-#define CALL(NC)                                                                                   \
+  if (cols > 8192 || cols % 8 || rows <= 0) return hipErrorInvalidValue;
+  const int vecs = cols / 8;
+#define CALL(BS, NC)                                                                               \
   if (dtype == 1)                                                                                  \
-    hipLaunchKernelGGL((layernorm_fwd_kernel<bf16_t, NC>), grid, block, 0, st,                     \
+    hipLaunchKernelGGL((layernorm_fwd_kernel<bf16_t, BS, NC>), dim3(rows), dim3(BS), 0, st,        \
                        static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(gamma),           \
                        static_cast<const bf16_t*>(beta), static_cast<bf16_t*>(y), mean, rstd,      \
                        rows, cols, eps);                                                           \
   else                                                                                             \
-    hipLaunchKernelGGL((layernorm_fwd_kernel<float, NC>), grid, block, 0, st,                      \
+    hipLaunchKernelGGL((layernorm_fwd_kernel<float, BS, NC>), dim3(rows), dim3(BS), 0, st,         \
                        static_cast<const float*>(x), static_cast<const float*>(gamma),             \
                        static_cast<const float*>(beta), static_cast<float*>(y), mean, rstd, rows,  \
                        cols, eps)
-  if (nc <= 1) { CALL(1); }
-  else if (nc <= 2) { CALL(2); }
-  else if (nc <= 4) { CALL(4); }
-  else if (nc <= 6) { CALL(6); }
-  else if (nc <= 8) { CALL(8); }
-  else if (nc <= 10) { CALL(10); }
-  else if (nc <= 12) { CALL(12); }
-  else { CALL(16); }
+  // up to four vectors per thread
+  if (vecs <= 64) { CALL(64, 1); }
+  else if (vecs <= 128) { CALL(64, 2); }
+  else if (vecs <= 256) { CALL(64, 4); }
+  else if (vecs <= 512) { CALL(128, 4); }
+  else if (vecs <= 768) { CALL(256, 3); }
+  else { CALL(256, 4); }
 #undef CALL
   return hipGetLastError();
 }
@@ -224,12 +259,12 @@ hipError_t layernorm_bwd(int dtype, const void* dy, const void* x, const float* 
   const int nc = (cols / 8 + kBwdThreads - 1) / kBwdThreads;
 #define CALL(NC)                                                                                   \
   if (dtype == 1)                                                                                  \
-    hipLaunchKernelGGL((layernorm_bwd_kernel<bf16_t, NC>), dim3(nb), dim3(kBwdThreads), 0, st,     \
+    hipLaunchKernelGGL((layernorm_bwd_kernel<bf16_t, NC, kBwdRowsPerIter>), dim3(nb), dim3(kBwdThreads), 0, st,     \
                        static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,  \
                        static_cast<const bf16_t*>(gamma), static_cast<const bf16_t*>(dres),        \
                        static_cast<bf16_t*>(dx_out), part_dg, part_db, rows, cols);                \
   else                                                                                             \
-    hipLaunchKernelGGL((layernorm_bwd_kernel<float, NC>), dim3(nb), dim3(kBwdThreads), 0, st,      \
+    hipLaunchKernelGGL((layernorm_bwd_kernel<float, NC, kBwdRowsPerIter>), dim3(nb), dim3(kBwdThreads), 0, st,      \
                        static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,    \
                        static_cast<const float*>(gamma), static_cast<const float*>(dres),          \
                        static_cast<float*>(dx_out), part_dg, part_db, rows, cols)
