@@ -79,6 +79,28 @@ __device__ __forceinline__ void wait_lgkmcnt0() {
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
+// An MFMA operand fragment as it arrives from LDS.  K-major slabs are read with plain
+// 16-byte loads, which the compiler tracks.  MN-major slabs are read with the transposing
+// LDS read, issued as inline assembly: the compiler's hazard tracking takes that read, as
+// a builtin, to alias every direct-to-LDS load in flight and waits for all of them
+// (vmcnt(0)) before it, which empties the prefetch ring once per slab.  The kernel's own
+// lgkmcnt waits cover these reads; settle(), called after such a wait, makes every later
+// use of the registers depend on a point after it.
+template <bool KMAJOR> struct Frag;
+template <> struct Frag<true> {
+  bf16x8_t v;
+  __device__ __forceinline__ bf16x8_t operand() const { return v; }
+  __device__ __forceinline__ void settle() {}
+};
+template <> struct Frag<false> {
+  short4_t lo, hi;
+  __device__ __forceinline__ bf16x8_t operand() const {
+    const short8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8_t, v);
+  }
+  __device__ __forceinline__ void settle() { asm volatile("" : "+v"(lo), "+v"(hi)); }
+};
+
 // One slab (ROWS x 32 elements) of an operand.
 template <int ROWS, bool KMAJOR>
 struct Slab {
@@ -106,11 +128,12 @@ struct Slab {
 
   // MFMA operand fragment: 8 consecutive k (at 16 ks + 8 (lane / 32)) of slab
   // row tile_row0 + lane % 32.
-  __device__ static __forceinline__ bf16x8_t fragment(const bf16_t* slab, int tile_row0, int ks, int lane) {
-    if (KMAJOR) {
+  __device__ static __forceinline__ Frag<KMAJOR> fragment(const bf16_t* slab, int tile_row0, int ks, int lane) {
+    Frag<KMAJOR> f;
+    if constexpr (KMAJOR) {
       const int r = tile_row0 + (lane & 31);
       const int chunk = (2 * ks + (lane >> 5)) ^ ((r >> 1) & 3);
-      return *reinterpret_cast<const bf16x8_t*>(slab + r * kBK + chunk * 8);
+      f.v = *reinterpret_cast<const bf16x8_t*>(slab + r * kBK + chunk * 8);
     } else {
       // four blocks of 16 lanes: block b holds rows (b & 1) * 16.. of k-group b >> 1; in a
       // block, lane i points at k-row i / 4, columns 4 (i % 4)..+3 and receives column i.
@@ -119,12 +142,12 @@ struct Slab {
       const int col = tile_row0 + (b & 1) * 16 + ((i & 3) << 2);
       const int sw = (k & 3) << 1;  // same for k and k + 4
       const bf16_t* p = slab + k * ROWS + (((col >> 3) ^ sw) << 3) + (col & 7);
-      typedef __attribute__((address_space(3))) short4_t* lds_ptr_t;
-      const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
-      const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * ROWS));
-      const short8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      return __builtin_bit_cast(bf16x8_t, v);
+      typedef const __attribute__((address_space(3))) bf16_t* lds_ptr_t;
+      const uint32_t addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)(p)));
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(4 * ROWS * 2));
     }
+    return f;
   }
 };
 
@@ -246,7 +269,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
   else wait_vmcnt<0>();
   block_barrier();
 
-  bf16x8_t fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  Frag<A_KMAJOR> fa0[TM], fa1[TM];
+  Frag<B_KMAJOR> fb0[TN], fb1[TN];
   {
     const bf16_t* sa = smem;
     const bf16_t* sb = sa + SA::kElems;
@@ -274,7 +298,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
       const int i = m / TM, j = m % TM;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i], fa0[j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb0[i].operand(), fa0[j].operand(), acc[i][j], 0, 0, 0);
 #pragma unroll
       for (int u = 0; u < kPer1; ++u) {
         const int op = m * kPer1 + u;
@@ -291,13 +315,17 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
     else wait_vmcnt<0>();
     wait_lgkmcnt0();
     block_barrier();
+#pragma unroll
+    for (int j = 0; j < TM; ++j) fa1[j].settle();
+#pragma unroll
+    for (int i = 0; i < TN; ++i) fb1[i].settle();
     const bool more = steady || kt + 1 < nk;
     const bf16_t* na = smem + ((kt + 1) & (kStages - 1)) * kStageElems;
     const bf16_t* nb = na + SA::kElems;
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
       const int i = m / TM, j = m % TM;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i], fa1[j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[i].operand(), fa1[j].operand(), acc[i][j], 0, 0, 0);
 #pragma unroll
       for (int u = 0; u < kPer2; ++u) {
         const int op = m * kPer2 + u;
@@ -308,9 +336,19 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_lgkmcnt0();  // tells the compiler nothing is pending at the loop top
+    wait_lgkmcnt0();  // the next slab's first fragments have arrived
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fa0[j].settle();
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fb0[i].settle();
+    }
   };
   wait_lgkmcnt0();
+#pragma unroll
+  for (int j = 0; j < TM; ++j) fa0[j].settle();
+#pragma unroll
+  for (int i = 0; i < TN; ++i) fb0[i].settle();
   int kt = 0;
   for (; kt + 3 < nk; ++kt) slab_step(kt, std::true_type{});
   for (; kt < nk; ++kt) slab_step(kt, std::false_type{});
