@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--policy", default=None, choices=list(POLICIES))
+    ap.add_argument("--retain-mask", default=None,
+                    help="explicit retain mask (hex), e.g. one of the six-layer slice's per-layer masks; overrides --policy")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (the known-size kernel that "
@@ -146,6 +148,10 @@ def main():
     cfg = synth.CONFIGS[args.config]
     policy = args.policy or {"C3": "elementwise_only", "C2": "full"}.get(args.config, "full")
     mask = POLICIES[policy]
+    if args.retain_mask is not None:
+        mask = (int(args.retain_mask, 16) & 0x3FFF) | 1
+        policy = "mask_0x%04x" % mask
+        POLICIES[policy] = mask
     tdtype = torch.bfloat16 if cfg.dtype == synth.BF16 else torch.float32
 
     def dev(a):
@@ -188,6 +194,8 @@ def main():
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     rec_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
     bwd_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+    per_step = sorted(e[1].elapsed_time(e[3]) for e in events)
+    median_ms, min_ms = per_step[len(per_step) // 2], per_step[0]
 
     # per-kernel durations: the same steps again with the library's event pairs on
     B.lynx_layer_set_profiling(layer, True)
@@ -254,6 +262,7 @@ def main():
                             "each step also runs lynx_layer_forward first (forward_ms, inside wall_ms_per_step)"},
         "recompute_ms": round(rec_ms, 4), "backward_ms": round(bwd_ms, 4), "forward_ms": round(fwd_ms, 4),
         "wall_ms_per_step": round(wall_ms, 4),
+        "median_ms_per_step": round(median_ms, 4), "min_ms_per_step": round(min_ms, 4),
         "algorithmic_tflop": {"forward": fwd_f / 1e12, "recompute": rec_f / 1e12, "backward": bwd_f / 1e12},
         "roofline": roofline,
         "kernels": kernels,
