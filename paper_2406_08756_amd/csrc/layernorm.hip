@@ -41,29 +41,29 @@ layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
   int r = blockIdx.x;
   if ((rows & 7) == 0) r = (r & 7) * (rows >> 3) + (r >> 3);
   const size_t base = static_cast<size_t>(r) * cols;
+  // Threads past the end of the row load column 0 again and count for nothing, so the
+  // loads and the arithmetic are straight-line code; only the stores are predicated.
   float v[NC][8];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
     const int j0 = (threadIdx.x + c * BS) * 8;
-    if (j0 < cols) {
-      load8(x + base + j0, v[c]);
+    const bool on = j0 < cols;
+    load8(x + base + (on ? j0 : 0), v[c]);
+    const float w = on ? 1.0f : 0.0f;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) sum += v[c][k];
-    }
+    for (int k = 0; k < 8; ++k) sum += w * v[c][k];
   }
   const float inv_n = 1.0f / static_cast<float>(cols);
   const float mu = block_sum<BS>(sum, red[0]) * inv_n;
   float sq = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int j0 = (threadIdx.x + c * BS) * 8;
-    if (j0 < cols) {
+    const float w = (threadIdx.x + c * BS) * 8 < cols ? 1.0f : 0.0f;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        v[c][k] -= mu;
-        sq += v[c][k] * v[c][k];
-      }
+    for (int k = 0; k < 8; ++k) {
+      v[c][k] -= mu;
+      sq += w * (v[c][k] * v[c][k]);
     }
   }
   const float rs = rsqrtf(block_sum<BS>(sq, red[1]) * inv_n + eps);
