@@ -197,6 +197,63 @@ lynx_status lynx_layer_set_profiling(lynx_layer_t layer, int on);
 lynx_status lynx_layer_profile_ms(lynx_layer_t layer, float* ms_out /* [LYNX_PROFILE_SLOTS], host */);
 const char* lynx_profile_slot_name(int slot);
 
+/* ---- Single-layer recomputation policy (Sec. 4.2, "Lynx-HEU") ------------
+ * Host only; no GPU is touched.  A layer of n_ops operators OP_1..OP_n; all
+ * masks use bit i for OP_i (bit 0 is the layer input and is ignored on input).
+ * The program solved is the paper's: minimise the regeneration time left on
+ * the critical path, sum_i (1 - S_i) R_{5,i} C_i (Eq. objective2), subject to
+ *   - each regenerated operator runs in exactly one phase (Eq. cons11);
+ *   - OP_i may run in phase t only if each input OP_j is retained or was
+ *     regenerated in a phase <= t, for every edge j -> i (Eq. cons12);
+ *   - the time placed in phase t <= 4 fits the communication it overlaps,
+ *     CTime_t (Eq. cons13); operators in comm_mask only run in phase 5 (cons14);
+ *   - m_static + n_layer n_batch sum_i S_i M_i
+ *       + n_layer sum_i (1 - S_i)(R_{1,i} + R_{2,i}) M_i <= m_budget
+ *     (Eq. cons15-17), with S_n = 1;
+ *   - last_stage != 0: phases 1 and 2 do not exist and the third memory term
+ *     is dropped ("Optimizations").
+ * Where the text sums Eq. cons11 over every operator, an operator is
+ * regenerated here only when required: needed_mask names the operators whose
+ * outputs backward reads; a discarded one must be regenerated, and so must
+ * every discarded input of a regenerated operator.  needed_mask = all ones
+ * gives the model exactly as printed.
+ * Exact search, exponential in n_ops (n_ops <= 24; a GPT layer has 13).
+ * Among equal critical-path times the least total regenerated time wins, then
+ * the lower peak.  Returns LYNX_ERR_OOM when no policy fits the budget,
+ * LYNX_ERR_INVALID_ARG for null arrays, negative numbers, n_ops out of range
+ * or an input that is not an earlier operator. */
+typedef struct {
+  int32_t n_ops;
+  const double* cost;      /* C_i, any time unit, n_ops entries (host) */
+  const double* bytes;     /* M_i, n_ops entries (host) */
+  const uint32_t* parents; /* n_ops masks: bit j of parents[i-1] = OP_j feeds OP_i, j < i (host) */
+  uint32_t comm_mask;
+  uint32_t needed_mask;
+  double ctime[4];         /* CTime_1..4, same unit as cost */
+  double m_budget, m_static;
+  int32_t n_layer, n_batch;
+  int32_t last_stage;
+} lynx_policy_problem;
+
+typedef struct {
+  uint32_t retain_mask;    /* S_i; bit 0 always set; usable as a forward retain mask */
+  uint32_t phase_mask[5];  /* operators regenerated in phase 1..5; 1..4 usable as recompute segments */
+  double critical_cost;    /* the objective */
+  double recompute_cost;   /* time regenerated over all five phases */
+  double peak_bytes;       /* left side of Eq. cons15 */
+} lynx_policy;
+
+lynx_status lynx_policy_solve(const lynx_policy_problem* problem, lynx_policy* policy_out);
+
+/* Fills the layer-shaped parts of a problem for this library's 13-operator
+ * block: n_ops = 13, parents, needed_mask (what lynx_layer_backward reads),
+ * comm_mask = 0 (a shard has no communication operator) and bytes = M_i of
+ * `cfg` (lynx_activation_bytes).  parents_out[13] and bytes_out[13] are caller
+ * arrays the problem will point into; cost, ctime, budget and counts stay the
+ * caller's to set.  Errors: INVALID_ARG, SHAPE. */
+lynx_status lynx_policy_layer_problem(const lynx_layer_config* cfg, lynx_policy_problem* problem_out,
+                                      uint32_t* parents_out, double* bytes_out);
+
 const char* lynx_status_string(lynx_status status);
 
 #ifdef __cplusplus

@@ -49,6 +49,18 @@ class lynx_grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
 
 
+class lynx_policy_problem(C.Structure):
+    _fields_ = [("n_ops", C.c_int32), ("cost", C.POINTER(C.c_double)), ("bytes", C.POINTER(C.c_double)),
+                ("parents", C.POINTER(C.c_uint32)), ("comm_mask", C.c_uint32), ("needed_mask", C.c_uint32),
+                ("ctime", C.c_double * 4), ("m_budget", C.c_double), ("m_static", C.c_double),
+                ("n_layer", C.c_int32), ("n_batch", C.c_int32), ("last_stage", C.c_int32)]
+
+
+class lynx_policy(C.Structure):
+    _fields_ = [("retain_mask", C.c_uint32), ("phase_mask", C.c_uint32 * 5), ("critical_cost", C.c_double),
+                ("recompute_cost", C.c_double), ("peak_bytes", C.c_double)]
+
+
 class LynxError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -79,6 +91,9 @@ _proto = {
     "lynx_layer_profile_ms": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "lynx_profile_slot_name": (C.c_char_p, [C.c_int]),
     "lynx_status_string": (C.c_char_p, [C.c_int]),
+    "lynx_policy_solve": (C.c_int, [C.POINTER(lynx_policy_problem), C.POINTER(lynx_policy)]),
+    "lynx_policy_layer_problem": (C.c_int, [_cfg_p, C.POINTER(lynx_policy_problem), C.POINTER(C.c_uint32),
+                                            C.POINTER(C.c_double)]),
 }
 for _name, (_res, _args) in _proto.items():
     _f = getattr(_lib, _name)
@@ -216,3 +231,62 @@ def lynx_layer_profile_ms(layer: int):
 
 def lynx_profile_slot_name(slot: int) -> str:
     return _lib.lynx_profile_slot_name(slot).decode()
+
+
+def _mask_of(indices) -> int:
+    m = 0
+    for i in indices:
+        m |= 1 << int(i)
+    return m
+
+
+def lynx_policy_solve(problem: dict):
+    """Solve a single-layer recomputation policy.  `problem` is a dict with n,
+    cost[n], bytes[n], parents[n] (tuples of 1-based operator indices), comm and
+    needed (sets of 1-based indices), ctime[4], m_budget, m_static, n_layer,
+    n_batch, last_stage.  Returns a dict (retain_mask, phase_mask[5],
+    critical_cost, recompute_cost, peak_bytes), or None when nothing fits."""
+    n = int(problem["n"])
+    cost = (C.c_double * n)(*[float(v) for v in problem["cost"]])
+    nbytes = (C.c_double * n)(*[float(v) for v in problem["bytes"]])
+    parents = (C.c_uint32 * n)(*[_mask_of(q) for q in problem["parents"]])
+    p = lynx_policy_problem()
+    p.n_ops = n
+    p.cost, p.bytes, p.parents = cost, nbytes, parents
+    p.comm_mask, p.needed_mask = _mask_of(problem["comm"]), _mask_of(problem["needed"])
+    for t in range(4):
+        p.ctime[t] = float(problem["ctime"][t])
+    p.m_budget, p.m_static = float(problem["m_budget"]), float(problem["m_static"])
+    p.n_layer, p.n_batch = int(problem["n_layer"]), int(problem["n_batch"])
+    p.last_stage = 1 if problem["last_stage"] else 0
+    out = lynx_policy()
+    st = _lib.lynx_policy_solve(C.byref(p), C.byref(out))
+    if st == LYNX_ERR_OOM:
+        return None
+    if st != LYNX_OK:
+        raise LynxError(st, "lynx_policy_solve")
+    return {"retain_mask": int(out.retain_mask), "phase_mask": [int(m) for m in out.phase_mask],
+            "critical_cost": float(out.critical_cost), "recompute_cost": float(out.recompute_cost),
+            "peak_bytes": float(out.peak_bytes)}
+
+
+def lynx_policy_layer_problem(cfg, cost, ctime, m_budget, m_static=0.0, n_layer=1, n_batch=1,
+                              last_stage=False) -> dict:
+    """The problem dict of this library's 13-operator block for `cfg`: the
+    dependency table, what backward reads and the M_i come from the library;
+    cost[13] (C_i of OP_1..OP_13, e.g. from lynx_layer_profile_ms) and the rest
+    from the caller."""
+    c = cfg if isinstance(cfg, lynx_layer_config) else make_config(cfg)
+    p = lynx_policy_problem()
+    parents = (C.c_uint32 * 13)()
+    nbytes = (C.c_double * 13)()
+    st = _lib.lynx_policy_layer_problem(C.byref(c), C.byref(p), parents, nbytes)
+    if st != LYNX_OK:
+        raise LynxError(st, "lynx_policy_layer_problem")
+    if len(cost) != 13:
+        raise ValueError("cost must have 13 entries (OP_1..OP_13)")
+    return {"n": 13, "cost": [float(v) for v in cost], "bytes": [float(v) for v in nbytes],
+            "parents": [tuple(j for j in range(1, 14) if (int(parents[i]) >> j) & 1) for i in range(13)],
+            "comm": set(), "needed": set(i for i in range(1, 14) if (int(p.needed_mask) >> i) & 1),
+            "ctime": [float(v) for v in ctime], "m_budget": float(m_budget), "m_static": float(m_static),
+            "n_layer": int(n_layer), "n_batch": int(n_batch), "last_stage": bool(last_stage)}

@@ -770,6 +770,26 @@ const char* lynx_profile_slot_name(int slot) {
   return (slot >= 1 && slot < kNumSlots) ? kSlotNames[slot] : "";
 }
 
+lynx_status lynx_policy_layer_problem(const lynx_layer_config* cfg, lynx_policy_problem* problem_out,
+                                      uint32_t* parents_out, double* bytes_out) {
+  if (cfg == nullptr || problem_out == nullptr || parents_out == nullptr || bytes_out == nullptr)
+    return LYNX_ERR_INVALID_ARG;
+  Dims D;
+  if (!make_dims(cfg, &D)) return LYNX_ERR_SHAPE;
+  for (int i = 1; i <= kNumOps; ++i) {
+    uint32_t m = 0;
+    for (int k = 0; k < 3 && kParents[i][k] >= 0; ++k) m |= 1u << kParents[i][k];
+    parents_out[i - 1] = m;
+    bytes_out[i - 1] = static_cast<double>(act_bytes(D, i));
+  }
+  problem_out->n_ops = kNumOps;
+  problem_out->parents = parents_out;
+  problem_out->bytes = bytes_out;
+  problem_out->needed_mask = kBackwardNeeds;
+  problem_out->comm_mask = 0;
+  return LYNX_OK;
+}
+
 const char* lynx_status_string(lynx_status s) {
   switch (s) {
     case LYNX_OK: return "ok";

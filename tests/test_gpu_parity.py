@@ -181,6 +181,50 @@ def test_explicit_segments_in_phases_then_backward():
     layer.close()
 
 
+def test_solved_policies_run_through_the_layer():
+    """Policies from lynx_policy_solve (Sec. 4.2): the retain mask drives the forward,
+    phase masks 1-4 are handed to lynx_recompute in order, phase 5 is left to backward;
+    every segment's inputs are there when it runs, the resident bytes after forward are
+    sum_i S_i M_i, and the gradients are the store-all bits."""
+    cfg = SMALL["tiles_bf16"]
+    params = synth.make_params(cfg, random_ln=True)
+    X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
+    layer = GpuLayer(cfg, params, workspace_bytes=2 * GpuLayer(cfg, params).B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
+    B = layer.B
+    layer.forward(X, pm.STORE_ALL)
+    layer.backward(dOUT)
+    torch.cuda.synchronize()
+    ref_dx = layer.dx.clone()
+    ref_grads = {k: v.clone() for k, v in layer.grads.items()}
+    M = pm.activation_bytes(cfg)
+    cost = [1.0, 6.0, 1.5, 1.2, 0.0, 1.5, 2.0, 1.0, 1.0, 8.0, 0.5, 8.0, 1.0]
+    seen = set()
+    for frac, ctime in [(0.0, [0, 0, 0, 0]), (0.0, [0, 0, 4.0, 9.0]), (0.3, [2.0, 2.0, 3.0, 3.0]),
+                        (0.6, [0, 0, 2.0, 2.0]), (0.15, [8.0, 0, 0, 8.0]), (0.5, [3.0, 3.0, 0, 0]),
+                        (1.0, [0, 0, 0, 0])]:
+        budget = M[13] + frac * sum(M[1:13])
+        prob = B.lynx_policy_layer_problem(cfg, cost, ctime=ctime, m_budget=budget + 1.0)
+        pol = B.lynx_policy_solve(prob)
+        assert pol is not None
+        seen.add((pol["retain_mask"], tuple(pol["phase_mask"])))
+        layer.dx.zero_()
+        for v in layer.grads.values():
+            v.zero_()
+        layer.forward(X, pol["retain_mask"])
+        kept = sum(M[i] for i in range(1, 13) if (pol["retain_mask"] >> i) & 1)
+        assert B.lynx_layer_live_bytes(layer.handle) == kept
+        for t in range(4):
+            if pol["phase_mask"][t]:
+                layer.recompute(pol["phase_mask"][t])
+        layer.backward(dOUT)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.dx, ref_dx), pol
+        for k, v in layer.grads.items():
+            assert torch.equal(v, ref_grads[k]), (pol, k)
+    assert len(seen) >= 4   # the instances really exercise different schedules
+    layer.close()
+
+
 def test_zero_output_projections_make_layer_identity_on_gpu():
     cfg = SMALL["tiles_bf16"]
     params = synth.make_params(cfg)
