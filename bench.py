@@ -129,6 +129,13 @@ def main():
     ap.add_argument("--policy", default=None, choices=list(POLICIES))
     ap.add_argument("--retain-mask", default=None,
                     help="explicit retain mask (hex), e.g. one of the six-layer slice's per-layer masks; overrides --policy")
+    ap.add_argument("--heu", action="store_true",
+                    help="choose the policy with lynx_policy_solve (Sec. 4.2) from operator times measured "
+                         "in this run; see --budget-frac and --ctime-ms")
+    ap.add_argument("--budget-frac", type=float, default=0.25,
+                    help="--heu: memory budget = checkpoint + this fraction of the store-all activations")
+    ap.add_argument("--ctime-ms", default="0.27,0.27,0.27,0.27",
+                    help="--heu: the four communication windows CTime_1..4 in ms (modelled, one GPU)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (the known-size kernel that "
@@ -169,11 +176,57 @@ def main():
     B.lynx_layer_set_params(layer, params)
     stream = torch.cuda.current_stream()
 
+    segments = [B.LYNX_SEG_ALL_MISSING]
+    heu = None
+    if args.heu:
+        # C_i: each forward operator's time under store-all, from the library's event pairs
+        full_ws = torch.empty(B.lynx_workspace_bytes(cfg, POLICIES["store_all"]) + 256, dtype=torch.uint8, device="cuda")
+        prof = B.lynx_layer_create(cfg, (full_ws.data_ptr() + 255) // 256 * 256, full_ws.numel() - 256)
+        B.lynx_layer_set_params(prof, params)
+        B.lynx_layer_set_profiling(prof, True)
+        cost = [0.0] * 13
+        reps = 5
+        for k in range(reps + 2):
+            B.lynx_layer_forward(prof, x, out, POLICIES["store_all"], k, stream)
+            ms = B.lynx_layer_profile_ms(prof)
+            B.lynx_layer_reset(prof)
+            if k >= 2:
+                for name, v in ms.items():
+                    if name.startswith("op"):
+                        cost[int(name[2:].split("_")[0]) - 1] += v / reps
+        B.lynx_layer_destroy(prof)
+        del full_ws
+        # the store-all forward runs OP4 and OP5 as one kernel (its time is under OP4): split it evenly
+        cost[3], cost[4] = 0.5 * cost[3], 0.5 * cost[3]
+        M = [B.lynx_activation_bytes(cfg, i) for i in range(14)]
+        budget = M[13] + args.budget_frac * sum(M[1:13])
+        ctime = [float(v) for v in args.ctime_ms.split(",")]
+        prob = B.lynx_policy_layer_problem(cfg, cost, ctime=ctime, m_budget=budget)
+        heu = B.lynx_policy_solve(prob)
+        if heu is None:
+            log("bench.py: no policy fits the budget")
+            sys.exit(1)
+        mask = heu["retain_mask"]
+        policy = "heu_0x%04x" % mask
+        POLICIES[policy] = mask
+        # phases 1-4 are what the communication windows would hide; phase 5 is left to backward
+        segments = [m for m in heu["phase_mask"][:4] if m]
+        heu = dict(heu, cost_ms=[round(c, 4) for c in cost], ctime_ms=ctime, budget_bytes=budget,
+                   phase_ops=[[i for i in range(1, 14) if (m >> i) & 1] for m in heu["phase_mask"]])
+        log("bench: HEU policy retain 0x%04x phases %s critical %.3f ms of %.3f ms regenerated" % (
+            mask, heu["phase_ops"], heu["critical_cost"], heu["recompute_cost"]))
+        ws_bytes = max(ws_bytes, 2 * B.lynx_workspace_bytes(cfg, mask))   # several segments: not the canonical sequence
+        B.lynx_layer_destroy(layer)
+        ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+        layer = B.lynx_layer_create(cfg, (ws.data_ptr() + 255) // 256 * 256, ws_bytes)
+        B.lynx_layer_set_params(layer, params)
+
     def step(ev=None, k=0):
         if ev: ev[0].record(stream)
         B.lynx_layer_forward(layer, x, out, mask, k, stream)
         if ev: ev[1].record(stream)
-        B.lynx_recompute(layer, B.LYNX_SEG_ALL_MISSING, stream)
+        for seg in segments:
+            B.lynx_recompute(layer, seg, stream)
         if ev: ev[2].record(stream)
         B.lynx_layer_backward(layer, dout, dx, grads, stream)
         if ev: ev[3].record(stream)
@@ -209,7 +262,8 @@ def main():
     for k in range(args.steps):
         B.lynx_layer_forward(layer, x, out, mask, k, stream)
         collect("fwd/")
-        B.lynx_recompute(layer, B.LYNX_SEG_ALL_MISSING, stream)
+        for seg in segments:
+            B.lynx_recompute(layer, seg, stream)
         B.lynx_layer_backward(layer, dout, dx, grads, stream)
         collect("rec/")
     B.lynx_layer_set_profiling(layer, False)
@@ -267,6 +321,10 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if heu is not None:
+        # recompute_ms here is what phases 1-4 regenerate (hidden behind communication in the
+        # paper's schedule); backward_ms includes phase 5, the part left on the critical path
+        result["heu"] = heu
     if not args.no_cpu_baseline:
         log("bench: timing the CPU oracle on a bounded sample")
         result["cpu_baseline"] = cpu_baseline(cfg, policy)
