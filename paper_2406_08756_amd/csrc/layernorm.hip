@@ -12,7 +12,7 @@ namespace lynx {
 namespace {
 
 constexpr int kBwdThreads = 256;
-constexpr int kBwdMaxBlocks = 1024;
+constexpr int kBwdMaxBlocks = 512;
 
 // Sum over the BS threads of a workgroup, every thread gets the total; `slot` is this
 // call's own LDS row, so two calls need no barrier between them.  Fixed combination order.
