@@ -59,7 +59,7 @@ def slot_work(cfg):
         "op13_bias_dropout_add2": ("hbm", 3 * T * h * e),
         "b13_dropout_bwd": ("hbm", 2 * T * h * e), "b12_fc2_dgrad_wgrad": ("mfma", 2 * lin(h, f)),
         "b11_gelu_bwd": ("hbm", 3 * T * f * e), "b10_fc1_dgrad_wgrad": ("mfma", 2 * lin(f, h)),
-        "b9_layernorm2_bwd": ("hbm", 4 * T * h * e), "b8_dropout_bwd": ("hbm", 2 * T * h * e),
+        "b98_layernorm2_dropout_bwd": ("hbm", 5 * T * h * e),
         "b7_proj_dgrad_wgrad": ("mfma", 2 * lin(h, p)),
         "b6_dpd": ("mfma", att), "b6_dv": ("mfma", att), "b54_softmax_dropout_bwd": ("hbm", 3 * tri * e),
         "b3_dq": ("mfma", att), "b3_dk": ("mfma", att), "b2_qkv_dgrad_wgrad": ("mfma", 2 * lin(3 * p, h)),

@@ -32,6 +32,12 @@ hipError_t layernorm_bwd(int dtype, const void* dy, const void* x, const float* 
                          const float* rstd, const void* gamma, const void* dres, void* dx_out,
                          void* dgamma, void* dbeta, float* scratch, int rows, int cols,
                          hipStream_t st);
+// The same, and in the same pass the backward of the bias + dropout + residual operator
+// whose output the LayerNorm read: dropped = keep c round(dx_out), dbias = its column sums.
+hipError_t layernorm_bwd_dropout_bwd(int dtype, const void* dy, const void* x, const float* mean,
+                                     const float* rstd, const void* gamma, const void* dres, void* dx_out,
+                                     void* dgamma, void* dbeta, void* dropped, void* dbias, float* scratch,
+                                     int rows, int cols, int site, DropoutParams dp, hipStream_t st);
 
 // ---- attention softmax / dropout -----------------------------------------
 // P = softmax_{j<=i}(S * scale) (written if P != null), Pd = keep * P * c

@@ -4,8 +4,7 @@
 // wavefronts per row stream; each lane owns fixed columns so the per-column
 // sums for dgamma / dbeta accumulate in registers over the rows the workgroup
 // visits, and are then reduced over workgroups in a second fixed-order stage.
-#include "device_common.h"
-#include "kernels.h"
+#include "dropout_host.h"
 #include "reduce_partials.h"
 
 namespace lynx {
@@ -106,15 +105,25 @@ __device__ __forceinline__ void block_sum4(float (&v)[4], float* smem) {
 // before the reductions.  Loaded vectors stay in storage format (half the registers for
 // bf16) and are unpacked where used, once for the sums and once for the output, which
 // buys the occupancy that hides the load latency.
-template <typename T, int NC, int RPI>
+//
+// DROP: the row gradient just formed is also the output gradient of a bias + dropout +
+// residual operator (dx_out = d(X + keep (O + b) c)): the same pass writes
+// dO = keep c round(dx_out) to `dropped` and accumulates its column sums (the bias
+// gradient), which saves the separate pass that would read dx_out again.
+template <typename T, int NC, int RPI, bool DROP>
 __global__ void __launch_bounds__(kBwdThreads)
 layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                      const float* __restrict__ mean, const float* __restrict__ rstd,
                      const T* __restrict__ gamma, const T* dres, T* dx_out,
-                     float* __restrict__ part_dg, float* __restrict__ part_db, int rows, int cols) {
+                     float* __restrict__ part_dg, float* __restrict__ part_db, int rows, int cols,
+                     T* __restrict__ dropped, float* __restrict__ part_dbias, DropoutKey key) {
   __shared__ float smem[16];
   Raw8<T> graw[NC];
-  float adg[NC][8], adb[NC][8];
+  float adg[NC][8], adb[NC][8], adbias[DROP ? NC : 1][8];
+#pragma unroll
+  for (int c = 0; c < (DROP ? NC : 1); ++c)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) adbias[c][k] = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
     const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
@@ -195,6 +204,18 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
             o[k] = dr[k] + rs[q] * (gd[k] * g[k] - m1 - xh[k] * m2);
           }
           store8(dx_out + base + j0, o);
+          if (DROP) {
+            float d[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) d[k] = round_to_storage(o[k], static_cast<T*>(nullptr));
+            dropout_apply8(key, (base + j0) >> 3, d);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              d[k] = round_to_storage(d[k], static_cast<T*>(nullptr));
+              adbias[DROP ? c : 0][k] += d[k];
+            }
+            store8(dropped + base + j0, d);
+          }
         }
       }
     }
@@ -205,6 +226,7 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
     if (j0 < cols) {
       store8(part_dg + static_cast<size_t>(blockIdx.x) * cols + j0, adg[c]);
       store8(part_db + static_cast<size_t>(blockIdx.x) * cols + j0, adb[c]);
+      if (DROP) store8(part_dbias + static_cast<size_t>(blockIdx.x) * cols + j0, adbias[DROP ? c : 0]);
     }
   }
 }
@@ -245,41 +267,70 @@ hipError_t layernorm_fwd(int dtype, const void* x, const void* gamma, const void
 }
 
 size_t layernorm_bwd_scratch_bytes(int rows, int cols) {
-  return 2 * static_cast<size_t>(bwd_blocks(rows)) * cols * sizeof(float);
+  return 3 * static_cast<size_t>(bwd_blocks(rows)) * cols * sizeof(float);
 }
+
+namespace {
+
+template <typename T, bool DROP>
+hipError_t launch_bwd(const T* dy, const T* x, const float* mean, const float* rstd, const T* gamma,
+                      const T* dres, T* dx_out, T* dgamma, T* dbeta, float* scratch, int rows, int cols,
+                      T* dropped, T* dbias, DropoutKey key, hipStream_t st) {
+  const int nb = bwd_blocks(rows);
+  float* part_dg = scratch;
+  float* part_db = scratch + static_cast<size_t>(nb) * cols;
+  float* part_dbias = scratch + 2 * static_cast<size_t>(nb) * cols;
+  const int nc = (cols / 8 + kBwdThreads - 1) / kBwdThreads;
+#define CALL(NC)                                                                                     \
+  hipLaunchKernelGGL((layernorm_bwd_kernel<T, NC, kBwdRowsPerIter, DROP>), dim3(nb), dim3(kBwdThreads), 0, st, \
+                     dy, x, mean, rstd, gamma, dres, dx_out, part_dg, part_db, rows, cols, dropped,   \
+                     part_dbias, key)
+  if (nc <= 1) { CALL(1); }
+  else if (nc <= 2) { CALL(2); }
+  else if (nc <= 3) { CALL(3); }
+  else { CALL(4); }
+#undef CALL
+  launch_reduce_partials<T>(part_dg, dgamma, part_db, dbeta, nb, cols, st);
+  if (DROP) launch_reduce_partials<T>(part_dbias, dbias, nullptr, nullptr, nb, cols, st);
+  return hipGetLastError();
+}
+
+}  // namespace
 
 hipError_t layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean,
                          const float* rstd, const void* gamma, const void* dres, void* dx_out,
                          void* dgamma, void* dbeta, float* scratch, int rows, int cols,
                          hipStream_t st) {
   if (cols > 8192 || cols % 8) return hipErrorInvalidValue;
-  const int nb = bwd_blocks(rows);
-  float* part_dg = scratch;
-  float* part_db = scratch + static_cast<size_t>(nb) * cols;
-  const int nc = (cols / 8 + kBwdThreads - 1) / kBwdThreads;
-#define CALL(NC)                                                                                   \
-  if (dtype == 1)                                                                                  \
-    hipLaunchKernelGGL((layernorm_bwd_kernel<bf16_t, NC, kBwdRowsPerIter>), dim3(nb), dim3(kBwdThreads), 0, st,     \
-                       static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,  \
-                       static_cast<const bf16_t*>(gamma), static_cast<const bf16_t*>(dres),        \
-                       static_cast<bf16_t*>(dx_out), part_dg, part_db, rows, cols);                \
-  else                                                                                             \
-    hipLaunchKernelGGL((layernorm_bwd_kernel<float, NC, kBwdRowsPerIter>), dim3(nb), dim3(kBwdThreads), 0, st,      \
-                       static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,    \
-                       static_cast<const float*>(gamma), static_cast<const float*>(dres),          \
-                       static_cast<float*>(dx_out), part_dg, part_db, rows, cols)
-  if (nc <= 1) { CALL(1); }
-  else if (nc <= 2) { CALL(2); }
-  else if (nc <= 3) { CALL(3); }
-  else { CALL(4); }
-#undef CALL
+  const DropoutKey none{};
   if (dtype == 1)
-    launch_reduce_partials<bf16_t>(part_dg, static_cast<bf16_t*>(dgamma), part_db,
-                                   static_cast<bf16_t*>(dbeta), nb, cols, st);
-  else
-    launch_reduce_partials<float>(part_dg, static_cast<float*>(dgamma), part_db,
-                                  static_cast<float*>(dbeta), nb, cols, st);
-  return hipGetLastError();
+    return launch_bwd<bf16_t, false>(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,
+                                     static_cast<const bf16_t*>(gamma), static_cast<const bf16_t*>(dres),
+                                     static_cast<bf16_t*>(dx_out), static_cast<bf16_t*>(dgamma),
+                                     static_cast<bf16_t*>(dbeta), scratch, rows, cols, nullptr, nullptr, none, st);
+  return launch_bwd<float, false>(static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,
+                                  static_cast<const float*>(gamma), static_cast<const float*>(dres),
+                                  static_cast<float*>(dx_out), static_cast<float*>(dgamma),
+                                  static_cast<float*>(dbeta), scratch, rows, cols, nullptr, nullptr, none, st);
+}
+
+hipError_t layernorm_bwd_dropout_bwd(int dtype, const void* dy, const void* x, const float* mean,
+                                     const float* rstd, const void* gamma, const void* dres, void* dx_out,
+                                     void* dgamma, void* dbeta, void* dropped, void* dbias, float* scratch,
+                                     int rows, int cols, int site, DropoutParams dp, hipStream_t st) {
+  if (cols > 8192 || cols % 8) return hipErrorInvalidValue;
+  const DropoutKey key = make_dropout_key(dp, site);
+  if (dtype == 1)
+    return launch_bwd<bf16_t, true>(static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x), mean, rstd,
+                                    static_cast<const bf16_t*>(gamma), static_cast<const bf16_t*>(dres),
+                                    static_cast<bf16_t*>(dx_out), static_cast<bf16_t*>(dgamma),
+                                    static_cast<bf16_t*>(dbeta), scratch, rows, cols,
+                                    static_cast<bf16_t*>(dropped), static_cast<bf16_t*>(dbias), key, st);
+  return launch_bwd<float, true>(static_cast<const float*>(dy), static_cast<const float*>(x), mean, rstd,
+                                 static_cast<const float*>(gamma), static_cast<const float*>(dres),
+                                 static_cast<float*>(dx_out), static_cast<float*>(dgamma),
+                                 static_cast<float*>(dbeta), scratch, rows, cols,
+                                 static_cast<float*>(dropped), static_cast<float*>(dbias), key, st);
 }
 
 }  // namespace lynx

@@ -141,7 +141,7 @@ struct Ctx {  // one pass (rehearsal or real) of a call
 
 // profile slots: 1..13 = forward operators; then the backward kernels in order
 enum BackwardSlot {
-  kB13Dropout = 14, kB12Grads, kB11Gelu, kB10Grads, kB9LayerNorm, kB8Dropout, kB7Grads, kB6DPd,
+  kB13Dropout = 14, kB12Grads, kB11Gelu, kB10Grads, kB98LayerNormDropout, kB7Grads, kB6DPd,
   kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kNumSlots
 };
 static_assert(kNumSlots <= LYNX_PROFILE_SLOTS, "profile slots");
@@ -149,8 +149,8 @@ const char* const kSlotNames[kNumSlots] = {
     "", "op1_layernorm1", "op2_qkv_gemm", "op3_scores", "op4_softmax_dropout", "op5_attn_dropout",
     "op6_context", "op7_attn_proj_gemm", "op8_bias_dropout_add1", "op9_layernorm2", "op10_fc1_gemm",
     "op11_gelu", "op12_fc2_gemm", "op13_bias_dropout_add2", "b13_dropout_bwd",
-    "b12_fc2_dgrad_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad_wgrad", "b9_layernorm2_bwd",
-    "b8_dropout_bwd", "b7_proj_dgrad_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd", "b3_dq",
+    "b12_fc2_dgrad_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad_wgrad",
+    "b98_layernorm2_dropout_bwd", "b7_proj_dgrad_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd", "b3_dq",
     "b3_dk", "b2_qkv_dgrad_wgrad", "b2_bias_grad", "b1_layernorm1_bwd"};
 
 char* act_ptr(const Ctx& cx, int i) {
@@ -489,18 +489,18 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_LAUNCH(cx, kB10Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T, D.f, D.h),
                                                   linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f, D.h), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_du);
-  // B9: Y2 = LN2(X2); dX2 = dOUT + dLN
+  // B9: Y2 = LN2(X2); dX2 = dOUT + dLN.  B8 in the same pass: X2 = X + keep1 (O + bo) c,
+  // so dO = keep1 c dX2 and dbo = its column sums
   LYNX_TRY(alloc_temp(cx, th, &t_dx2));
-  LYNX_LAUNCH(cx, kB9LayerNorm, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy2), act_ptr(cx, 8), stats_ptr(cx, 9),
-                                      stats_ptr(cx, 9) + D.T, w.g2, d_out, temp_ptr(cx, t_dx2),
-                                      gr->g2, gr->be2, scr, D.T, D.h, cx.st));
+  LYNX_TRY(alloc_temp(cx, th, &t_do));
+  LYNX_LAUNCH(cx, kB98LayerNormDropout,
+              lynx::layernorm_bwd_dropout_bwd(dt, temp_ptr(cx, t_dy2), act_ptr(cx, 8), stats_ptr(cx, 9),
+                                              stats_ptr(cx, 9) + D.T, w.g2, d_out, temp_ptr(cx, t_dx2), gr->g2,
+                                              gr->be2, temp_ptr(cx, t_do), gr->bo, scr, D.T, D.h, 1,
+                                              dropout_params(L), cx.st));
   free_temp(cx, &t_dy2);
   free_act(cx, 9);
   free_act(cx, 8);
-  // B8: X2 = X + keep1 (O + bo) c
-  LYNX_TRY(alloc_temp(cx, th, &t_do));
-  LYNX_LAUNCH(cx, kB8Dropout, lynx::dropout_bwd(dt, temp_ptr(cx, t_dx2), temp_ptr(cx, t_do), gr->bo, scr, D.T,
-                                    D.h, 1, dropout_params(L), cx.st));
   // B7: O = C Wo^T
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * D.p * e, &t_dc));
   LYNX_LAUNCH(cx, kB7Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T, D.h, D.p),
