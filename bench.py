@@ -120,6 +120,71 @@ def cpu_baseline(cfg, retain_name):
                           small.micro_batch, cfg.micro_batch, t1 - t0, t2 - t1)}
 
 
+def slice_bench(args):
+    """The six-layer pipeline-stage slice (C5): six handles, forward 0 -> 5 under the seeded
+    per-layer masks, then the reverse sweep 5 -> 0 (regeneration + backward per layer), which
+    is what is timed.  Layer l's output buffer is layer l + 1's input."""
+    import torch
+    import lynx_synth as synth
+    from paper_2406_08756_amd import binding as B
+    base = synth.CONFIGS["C5"]
+    L, masks = synth.C5_LAYERS, synth.c5_retain_masks()
+    dev = lambda a: torch.from_numpy(a).to(torch.bfloat16).cuda()
+    stream = torch.cuda.current_stream()
+    layers, keep = [], []
+    x0, dout = dev(synth.make_x(base)), dev(synth.make_dout(base))
+    outs = [torch.empty_like(x0) for _ in range(L)]
+    dxs = [torch.empty_like(x0) for _ in range(L)]
+    for l in range(L):
+        cfg = base.with_(layer_id=l)
+        params = {k: dev(v) for k, v in synth.make_params(cfg).items()}
+        grads = {k: torch.empty_like(v) for k, v in params.items()}
+        nbytes = B.lynx_workspace_bytes(cfg, masks[l])
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        h = B.lynx_layer_create(cfg, (ws.data_ptr() + 255) // 256 * 256, nbytes)
+        B.lynx_layer_set_params(h, params)
+        layers.append(h)
+        keep.append((params, grads, ws, cfg))
+
+    def sweep(ev=None, k=0):
+        if ev: ev[0].record(stream)
+        for l in range(L):
+            B.lynx_layer_forward(layers[l], x0 if l == 0 else outs[l - 1], outs[l], masks[l], k, stream)
+        if ev: ev[1].record(stream)
+        for l in reversed(range(L)):
+            B.lynx_recompute(layers[l], B.LYNX_SEG_ALL_MISSING, stream)
+            B.lynx_layer_backward(layers[l], dout if l == L - 1 else dxs[l + 1], dxs[l], keep[l][1], stream)
+            if ev: ev[2 + (L - 1 - l)].record(stream)
+
+    for k in range(args.warmup):
+        sweep(None, k)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2 + L)] for _ in range(args.steps)]
+    for k in range(args.steps):
+        sweep(events[k], k)
+    torch.cuda.synchronize()
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    per_layer = [sum(e[1 + j].elapsed_time(e[2 + j]) for e in events) / args.steps for j in range(L)]  # layer 5 first
+    total = sum(per_layer)
+    flops = 0.0
+    for l in range(L):
+        POLICIES["m%d" % l] = masks[l]
+        _, rec_f, bwd_f = phase_flops(keep[l][3], masks[l])
+        flops += rec_f + bwd_f
+    for h in layers:
+        B.lynx_layer_destroy(h)
+    print(json.dumps({
+        "metric": "recompute+backward TFLOP/s per GPT layer shard", "value": round(flops / (total * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(total, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C5 slice: 6 layers h=%d a=%d d=%d f=%d s=%d b=%d tp=%d, seeded masks %s" % (
+            base.hidden, base.local_heads, base.head_dim, base.local_ffn, base.seq, base.micro_batch, base.tp_size,
+            " ".join("%04x" % m for m in masks)),
+            "timed_region": "reverse sweep: lynx_recompute + lynx_layer_backward for layers 5..0"},
+        "forward_sweep_ms": round(fwd_ms, 4),
+        "reverse_sweep_ms_per_layer": {"layer%d" % (L - 1 - j): round(v, 4) for j, v in enumerate(per_layer)}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,6 +201,8 @@ def main():
                     help="--heu: memory budget = checkpoint + this fraction of the store-all activations")
     ap.add_argument("--ctime-ms", default="0.27,0.27,0.27,0.27",
                     help="--heu: the four communication windows CTime_1..4 in ms (modelled, one GPU)")
+    ap.add_argument("--slice", action="store_true",
+                    help="time the six-layer pipeline-stage slice (C5) instead of one layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (the known-size kernel that "
@@ -152,6 +219,8 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(1)
+    if args.slice:
+        return slice_bench(args)
     cfg = synth.CONFIGS[args.config]
     policy = args.policy or {"C3": "elementwise_only", "C2": "full"}.get(args.config, "full")
     mask = POLICIES[policy]
