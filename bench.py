@@ -120,6 +120,66 @@ def cpu_baseline(cfg, retain_name):
                           small.micro_batch, cfg.micro_batch, t1 - t0, t2 - t1)}
 
 
+def overlap_measure(B, torch, layer, x, out, mask, segments, dout, dx, grads, main, workgroups, reps):
+    """The paper hides regeneration behind tensor-parallel communication (phases 1-4).  On one
+    GPU: the regeneration segments run on a side stream while a stand-in for the all-reduce
+    (a copy of one [T, h] tensor by a fixed number of workgroups) runs on the main stream.
+    Three timings per repetition, each after a fresh forward: stand-in alone, regeneration
+    alone, both at once (from a common start to the later of the two ends)."""
+    side = torch.cuda.Stream()          # default priority
+    src, dst = torch.empty_like(x), torch.empty_like(x)
+    nbytes = x.numel() * x.element_size()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_comm = t_rec = t_both = 0.0
+
+    def fresh_forward(k):
+        B.lynx_layer_forward(layer, x, out, mask, k, main)
+
+    def finish():
+        B.lynx_layer_backward(layer, dout, dx, grads, main)
+
+    for k in range(reps + 2):
+        # stand-in alone
+        fresh_forward(k)
+        a, b = ev(), ev()
+        a.record(main)
+        B.lynx_comm_standin(dst, src, nbytes, workgroups, main)
+        b.record(main)
+        # regeneration alone (on the side stream, as it would run)
+        c, d = ev(), ev()
+        c.record(main)
+        side.wait_event(c)
+        c2 = ev(); c2.record(side)
+        for seg in segments:
+            B.lynx_recompute(layer, seg, side)
+        d.record(side)
+        main.wait_event(d)
+        finish()
+        # both at once
+        fresh_forward(k)
+        e, f, g = ev(), ev(), ev()
+        e.record(main)
+        side.wait_event(e)
+        B.lynx_comm_standin(dst, src, nbytes, workgroups, main)
+        for seg in segments:
+            B.lynx_recompute(layer, seg, side)
+        f.record(side)
+        main.wait_event(f)
+        g.record(main)
+        finish()
+        torch.cuda.synchronize()
+        if k >= 2:
+            t_comm += a.elapsed_time(b) / reps
+            t_rec += c2.elapsed_time(d) / reps
+            t_both += e.elapsed_time(g) / reps
+    hidden = t_comm + t_rec - t_both
+    return {"standin_bytes": nbytes, "standin_workgroups": workgroups, "standin_alone_ms": round(t_comm, 4),
+            "standin_alone_gbs": round(2 * nbytes / (t_comm * 1e-3) / 1e9, 1),
+            "regeneration_alone_ms": round(t_rec, 4), "concurrent_ms": round(t_both, 4),
+            "hidden_ms": round(hidden, 4), "hidden_frac_of_shorter": round(hidden / max(min(t_comm, t_rec), 1e-9), 3),
+            "segments": ["0x%x" % (m & 0xFFFFFFFF) for m in segments]}
+
+
 def slice_bench(args):
     """The six-layer pipeline-stage slice (C5): six handles, forward 0 -> 5 under the seeded
     per-layer masks, then the reverse sweep 5 -> 0 (regeneration + backward per layer), which
@@ -201,6 +261,10 @@ def main():
                     help="--heu: memory budget = checkpoint + this fraction of the store-all activations")
     ap.add_argument("--ctime-ms", default="0.27,0.27,0.27,0.27",
                     help="--heu: the four communication windows CTime_1..4 in ms (modelled, one GPU)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="also measure regeneration on a side stream under a stand-in for the "
+                         "tensor-parallel all-reduce (lynx_comm_standin); adds an 'overlap' object")
+    ap.add_argument("--standin-workgroups", type=int, default=32)
     ap.add_argument("--slice", action="store_true",
                     help="time the six-layer pipeline-stage slice (C5) instead of one layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -336,6 +400,10 @@ def main():
         B.lynx_layer_backward(layer, dout, dx, grads, stream)
         collect("rec/")
     B.lynx_layer_set_profiling(layer, False)
+    overlap = None
+    if args.overlap:
+        overlap = overlap_measure(B, torch, layer, x, out, mask, segments, dout, dx, grads, stream,
+                                  args.standin_workgroups, max(args.steps, 5))
     B.lynx_layer_destroy(layer)
 
     work = slot_work(cfg)
@@ -390,6 +458,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if overlap is not None:
+        result["overlap"] = overlap
     if heu is not None:
         # recompute_ms here is what phases 1-4 regenerate (hidden behind communication in the
         # paper's schedule); backward_ms includes phase 5, the part left on the critical path

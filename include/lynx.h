@@ -254,6 +254,16 @@ lynx_status lynx_policy_solve(const lynx_policy_problem* problem, lynx_policy* p
 lynx_status lynx_policy_layer_problem(const lynx_layer_config* cfg, lynx_policy_problem* problem_out,
                                       uint32_t* parents_out, double* bytes_out);
 
+/* Measurement aid, not part of the method: a device copy of `bytes` (multiple of
+ * 16; both pointers device, 16-byte aligned, not overlapping) done by a fixed
+ * number of workgroups (1..4096), enqueued on `hip_stream`.  It stands in for the
+ * tensor-parallel all-reduce that the paper overlaps regeneration with (Sec. 4,
+ * phases 1-4) when that overlap is measured on one GPU: a bounded number of
+ * compute units and a bounded share of memory bandwidth, busy for a while.
+ * Errors: INVALID_ARG, HIP. */
+lynx_status lynx_comm_standin(void* dst_device, const void* src_device, size_t bytes, int workgroups,
+                              void* hip_stream);
+
 const char* lynx_status_string(lynx_status status);
 
 #ifdef __cplusplus

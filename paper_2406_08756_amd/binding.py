@@ -91,6 +91,7 @@ _proto = {
     "lynx_layer_profile_ms": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "lynx_profile_slot_name": (C.c_char_p, [C.c_int]),
     "lynx_status_string": (C.c_char_p, [C.c_int]),
+    "lynx_comm_standin": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]),
     "lynx_policy_solve": (C.c_int, [C.POINTER(lynx_policy_problem), C.POINTER(lynx_policy)]),
     "lynx_policy_layer_problem": (C.c_int, [_cfg_p, C.POINTER(lynx_policy_problem), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_double)]),
@@ -231,6 +232,11 @@ def lynx_layer_profile_ms(layer: int):
 
 def lynx_profile_slot_name(slot: int) -> str:
     return _lib.lynx_profile_slot_name(slot).decode()
+
+
+def lynx_comm_standin(dst, src, nbytes: int, workgroups: int, stream=None) -> None:
+    _check(_lib.lynx_comm_standin(_addr(dst), _addr(src), nbytes, workgroups, _stream(stream)),
+           "lynx_comm_standin")
 
 
 def _mask_of(indices) -> int:

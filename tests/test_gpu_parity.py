@@ -238,3 +238,22 @@ def test_zero_output_projections_make_layer_identity_on_gpu():
     assert np.array_equal(layer.out.float().cpu().numpy(), X)
     assert np.array_equal(got["dX"], dOUT.astype(np.float64))
     layer.close()
+
+
+def test_comm_standin_copies_and_checks_arguments():
+    from paper_2406_08756_amd import binding as B
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    B.lynx_comm_standin(dst, src, src.numel() * 4, 7)          # 7 workgroups, ragged share per workgroup
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    dst.zero_()
+    B.lynx_comm_standin(dst, src, 48, 1)                       # three vectors
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:12], src[:12]) and int(dst[12:].abs().sum()) == 0
+    for bad in [dict(nbytes=40, workgroups=1), dict(nbytes=64, workgroups=0), dict(nbytes=64, workgroups=5000)]:
+        with pytest.raises(B.LynxError) as e:
+            B.lynx_comm_standin(dst, src, bad["nbytes"], bad["workgroups"])
+        assert e.value.status == B.LYNX_ERR_INVALID_ARG
+    with pytest.raises(B.LynxError):
+        B.lynx_comm_standin(dst.data_ptr() + 4, src, 64, 1)    # misaligned
