@@ -374,6 +374,16 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
         }
     return;
   }
+  // The bias values of this wavefront's columns, requested in one batch (one exposed L2
+  // round trip instead of one per group of columns).
+  uint2 braw[TN][4];
+  if (g.bias != nullptr) {
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        braw[i][q] = *reinterpret_cast<const uint2*>(g.bias + n0 + wn0 + 32 * i + 8 * q + 4 * (lane >> 5));
+  }
   block_barrier();  // every wavefront is done with the ring (no load is in flight any more)
   constexpr int kRowChunks = WN / 8;
   bf16_t* stage = smem + wave * (WM * WN);
@@ -384,8 +394,8 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
       const int nl = 32 * i + 8 * q + 4 * (lane >> 5);
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
       if (g.bias != nullptr) {
-        const uint2 braw = *reinterpret_cast<const uint2*>(g.bias + n0 + wn0 + nl);
-        bv[0] = bf16_lo(braw.x); bv[1] = bf16_hi(braw.x); bv[2] = bf16_lo(braw.y); bv[3] = bf16_hi(braw.y);
+        const uint2 b = braw[i][q];
+        bv[0] = bf16_lo(b.x); bv[1] = bf16_hi(b.x); bv[2] = bf16_lo(b.y); bv[3] = bf16_hi(b.y);
       }
 #pragma unroll
       for (int j = 0; j < TM; ++j) {

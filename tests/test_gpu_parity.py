@@ -30,6 +30,13 @@ SMALL = {
     # sequence of two 256-tiles: the large score tiles and multi-slab causal contractions
     "tiles256_bf16": synth.LayerConfig(synth.BF16, 256, 2, 128, 256, 512, 1, tp_size=1,
                                        dropout_p=0.1, seed=6, layer_id=3),
+    # the longest rows the softmax kernels take in registers at half their limit, 32 row
+    # blocks in the contraction-restricted attention products
+    "long_seq_bf16": synth.LayerConfig(synth.BF16, 256, 1, 128, 256, 4096, 1, tp_size=1,
+                                       dropout_p=0.1, seed=8, layer_id=4),
+    # the widest rows the LayerNorm kernels accept (four vectors per thread), K = 8192 GEMMs
+    "wide_bf16": synth.LayerConfig(synth.BF16, 8192, 1, 128, 128, 128, 1, tp_size=1,
+                                   dropout_p=0.1, seed=12, layer_id=6),
     "C1": synth.CONFIGS["C1"],
     "nodrop_bf16": synth.LayerConfig(synth.BF16, 256, 2, 64, 512, 128, 1, dropout_p=0.0),
     "minimal_f32": synth.LayerConfig(synth.F32, 8, 1, 8, 8, 8, 1, dropout_p=0.5, seed=9),
@@ -96,7 +103,8 @@ def test_store_all_forward_and_backward_match_oracle(name):
     layer.close()
 
 
-@pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16", "tiles128_bf16", "tiles256_bf16"])
+@pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16", "tiles128_bf16", "tiles256_bf16", "long_seq_bf16",
+                                  "wide_bf16"])
 def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
     cfg = SMALL[name]
     params = synth.make_params(cfg, random_ln=True)
