@@ -245,6 +245,34 @@ typedef struct {
 
 lynx_status lynx_policy_solve(const lynx_policy_problem* problem, lynx_policy* policy_out);
 
+/* ---- Recomputation-aware model partitioning (Sec. 5) -----------------------
+ * Host only.  n_total_layers identical layers are dealt to n_stages pipeline
+ * stages by the section's greedy search: (1) equal shares (the remainder one
+ * each to the first stages); (2) every stage's policy from lynx_policy_solve;
+ * (3) every stage's time; (4) one layer moves from the slowest stage to the
+ * fastest; the move is kept if every stage still fits its memory and the
+ * slowest stage became faster; (5) otherwise the current scheme is the answer.
+ * The section prints no formula for its training cost model; the one used: a
+ * stage's time per micro-batch = its layers x (t_fwd + t_bwd + the policy's
+ * critical_cost), stage s holds n_stages - s forward passes before its first
+ * backward (one-forward-one-backward), the last stage uses the last-stage
+ * variant, and a stage's static bytes are static_per_layer x its layers.  Of
+ * `layer`, the fields n_layer, n_batch, last_stage, m_static and m_budget are
+ * ignored (set per stage).  layers_out[n_stages], time_out[n_stages] and, if
+ * not NULL, policies_out[n_stages] are caller arrays.  Errors: INVALID_ARG
+ * (also n_stages > 64 or fewer layers than stages), OOM when the equal-share
+ * scheme does not fit. */
+typedef struct {
+  const lynx_policy_problem* layer;
+  int32_t n_total_layers, n_stages;
+  double t_fwd, t_bwd;       /* per layer and micro-batch, same unit as layer->cost */
+  double static_per_layer;   /* bytes of weights, gradients and optimizer state per layer */
+  double m_budget;           /* bytes per GPU */
+} lynx_partition_problem;
+
+lynx_status lynx_partition_solve(const lynx_partition_problem* problem, int32_t* layers_out,
+                                 double* time_out, lynx_policy* policies_out);
+
 /* Fills the layer-shaped parts of a problem for this library's 13-operator
  * block: n_ops = 13, parents, needed_mask (what lynx_layer_backward reads),
  * comm_mask = 0 (a shard has no communication operator) and bytes = M_i of

@@ -97,3 +97,86 @@ def brute_force(problem):
             if best is None or val < best[0] - 1e-12:
                 best = (val, list(S), phase)
     return best
+
+
+# ---- recomputation-aware model partitioning (Sec. 5) --------------------------------
+# The greedy search of the section's "Key idea", steps (1)-(5), transcribed with the
+# brute-force policy search above as the Recomputation Policy Generator.  The section
+# gives no formula for the Training Cost Model; the reading used (here and in the
+# library) is: a stage's time per micro-batch is its number of layers times
+# (forward time + backward time + regeneration time left on the critical path), all per
+# layer; stage s of P holds N_batch = P - s forward passes before its first backward
+# (one-forward-one-backward schedule) and the last stage uses the last-stage variant of
+# the policy program; M_static of a stage is static_per_layer times its layers.  Step (1),
+# "approximately the same number of layers": floor(L / P) each, the remainder one each to
+# the first stages.  Ties for slowest / fastest go to the lowest stage index.
+def stage_time(layer_problem, n_layers, stage, n_stages, t_fwd, t_bwd, static_per_layer, m_budget):
+    """(time per micro-batch, policy) of one stage, or None when no policy fits."""
+    if n_layers == 0:
+        return 0.0, None
+    p = dict(layer_problem, n_layer=n_layers, n_batch=n_stages - stage, last_stage=(stage == n_stages - 1),
+             m_static=static_per_layer * n_layers, m_budget=m_budget)
+    best = brute_force(p)
+    if best is None:
+        return None
+    return n_layers * (t_fwd + t_bwd + best[0]), best
+
+
+def greedy_partition(layer_problem, n_total_layers, n_stages, t_fwd, t_bwd, static_per_layer, m_budget):
+    """Returns (layers per stage, stage times) or None when the initial scheme is invalid."""
+    base, extra = divmod(n_total_layers, n_stages)
+    layers = [base + (1 if s < extra else 0) for s in range(n_stages)]              # step (1)
+
+    def evaluate(scheme):                                                           # steps (2), (3)
+        times = []
+        for s, n in enumerate(scheme):
+            r = stage_time(layer_problem, n, s, n_stages, t_fwd, t_bwd, static_per_layer, m_budget)
+            if r is None:
+                return None
+            times.append(r[0])
+        return times
+
+    times = evaluate(layers)
+    if times is None:
+        return None
+    while True:
+        slow = max(range(n_stages), key=lambda s: (times[s], -s))
+        fast = min(range(n_stages), key=lambda s: (times[s], s))
+        if slow == fast or layers[slow] <= 1:
+            break
+        trial = list(layers)                                                        # step (4)
+        trial[slow] -= 1
+        trial[fast] += 1
+        t2 = evaluate(trial)
+        if t2 is None or max(t2) >= max(times) - 1e-12:
+            break
+        layers, times = trial, t2
+    return layers, times
+
+
+def best_partition_exhaustive(layer_problem, n_total_layers, n_stages, t_fwd, t_bwd, static_per_layer, m_budget):
+    """Minimum over every composition of the layers into non-empty stages of the slowest
+    stage's time: what the greedy search can at best reach."""
+    best = None
+
+    def rec(prefix, left):
+        nonlocal best
+        s = len(prefix)
+        if s == n_stages - 1:
+            scheme = prefix + [left]
+            if left < 1:
+                return
+            worst = 0.0
+            for st, n in enumerate(scheme):
+                r = stage_time(layer_problem, n, st, n_stages, t_fwd, t_bwd, static_per_layer, m_budget)
+                if r is None:
+                    return
+                worst = max(worst, r[0])
+            if best is None or worst < best[0] - 1e-12:
+                best = (worst, scheme)
+            return
+        for n in range(1, left - (n_stages - s - 1) + 1):
+            rec(prefix + [n], left - n)
+
+    rec([], n_total_layers)
+    return best

@@ -61,6 +61,12 @@ class lynx_policy(C.Structure):
                 ("recompute_cost", C.c_double), ("peak_bytes", C.c_double)]
 
 
+class lynx_partition_problem(C.Structure):
+    _fields_ = [("layer", C.POINTER(lynx_policy_problem)), ("n_total_layers", C.c_int32), ("n_stages", C.c_int32),
+                ("t_fwd", C.c_double), ("t_bwd", C.c_double), ("static_per_layer", C.c_double),
+                ("m_budget", C.c_double)]
+
+
 class LynxError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -93,6 +99,8 @@ _proto = {
     "lynx_status_string": (C.c_char_p, [C.c_int]),
     "lynx_comm_standin": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]),
     "lynx_policy_solve": (C.c_int, [C.POINTER(lynx_policy_problem), C.POINTER(lynx_policy)]),
+    "lynx_partition_solve": (C.c_int, [C.POINTER(lynx_partition_problem), C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_double), C.POINTER(lynx_policy)]),
     "lynx_policy_layer_problem": (C.c_int, [_cfg_p, C.POINTER(lynx_policy_problem), C.POINTER(C.c_uint32),
                                             C.POINTER(C.c_double)]),
 }
@@ -244,6 +252,52 @@ def _mask_of(indices) -> int:
     for i in indices:
         m |= 1 << int(i)
     return m
+
+
+def _policy_problem_struct(problem: dict):
+    """(struct, keep-alive arrays) for a problem dict."""
+    n = int(problem["n"])
+    cost = (C.c_double * n)(*[float(v) for v in problem["cost"]])
+    nbytes = (C.c_double * n)(*[float(v) for v in problem["bytes"]])
+    parents = (C.c_uint32 * n)(*[_mask_of(q) for q in problem["parents"]])
+    p = lynx_policy_problem()
+    p.n_ops = n
+    p.cost, p.bytes, p.parents = cost, nbytes, parents
+    p.comm_mask, p.needed_mask = _mask_of(problem["comm"]), _mask_of(problem["needed"])
+    for t in range(4):
+        p.ctime[t] = float(problem["ctime"][t])
+    p.m_budget, p.m_static = float(problem.get("m_budget", 0.0)), float(problem.get("m_static", 0.0))
+    p.n_layer, p.n_batch = int(problem.get("n_layer", 1)), int(problem.get("n_batch", 1))
+    p.last_stage = 1 if problem.get("last_stage") else 0
+    return p, (cost, nbytes, parents)
+
+
+def _policy_dict(out) -> dict:
+    return {"retain_mask": int(out.retain_mask), "phase_mask": [int(m) for m in out.phase_mask],
+            "critical_cost": float(out.critical_cost), "recompute_cost": float(out.recompute_cost),
+            "peak_bytes": float(out.peak_bytes)}
+
+
+def lynx_partition_solve(layer_problem: dict, n_total_layers: int, n_stages: int, t_fwd: float, t_bwd: float,
+                         static_per_layer: float, m_budget: float):
+    """Recomputation-aware greedy partition of identical layers over pipeline stages.
+    Returns (layers per stage, time per stage, policy per stage) or None when the
+    equal-share scheme does not fit the budget."""
+    p, keep = _policy_problem_struct(layer_problem)
+    pp = lynx_partition_problem()
+    pp.layer = C.pointer(p)
+    pp.n_total_layers, pp.n_stages = int(n_total_layers), int(n_stages)
+    pp.t_fwd, pp.t_bwd = float(t_fwd), float(t_bwd)
+    pp.static_per_layer, pp.m_budget = float(static_per_layer), float(m_budget)
+    layers = (C.c_int32 * n_stages)()
+    times = (C.c_double * n_stages)()
+    policies = (lynx_policy * n_stages)()
+    st = _lib.lynx_partition_solve(C.byref(pp), layers, times, policies)
+    if st == LYNX_ERR_OOM:
+        return None
+    if st != LYNX_OK:
+        raise LynxError(st, "lynx_partition_solve")
+    return [int(v) for v in layers], [float(v) for v in times], [_policy_dict(q) for q in policies]
 
 
 def lynx_policy_solve(problem: dict):

@@ -153,3 +153,85 @@ extern "C" lynx_status lynx_policy_solve(const lynx_policy_problem* p, lynx_poli
   *out = s.out;
   return LYNX_OK;
 }
+
+// ---- recomputation-aware model partitioning (Sec. 5) ------------------------------
+// The section's greedy search: start from equal shares, evaluate every stage with the
+// single-layer policy solver, move one layer from the slowest stage to the fastest,
+// keep the move if it is valid and the slowest stage got faster, stop otherwise.
+namespace {
+
+struct StageEval {
+  bool valid;
+  double time;
+  lynx_policy policy;
+};
+
+StageEval eval_stage(const lynx_partition_problem& pp, int stage, int n_layers) {
+  StageEval e;
+  memset(&e, 0, sizeof(e));
+  e.valid = true;
+  if (n_layers == 0) return e;
+  lynx_policy_problem p = *pp.layer;
+  p.n_layer = n_layers;
+  p.n_batch = pp.n_stages - stage;  // forward passes held before the first backward (1F1B)
+  p.last_stage = stage == pp.n_stages - 1;
+  p.m_static = pp.static_per_layer * n_layers;
+  p.m_budget = pp.m_budget;
+  if (lynx_policy_solve(&p, &e.policy) != LYNX_OK) {
+    e.valid = false;
+    return e;
+  }
+  e.time = n_layers * (pp.t_fwd + pp.t_bwd + e.policy.critical_cost);
+  return e;
+}
+
+}  // namespace
+
+extern "C" lynx_status lynx_partition_solve(const lynx_partition_problem* pp, int32_t* layers_out,
+                                            double* time_out, lynx_policy* policies_out) {
+  if (pp == nullptr || pp->layer == nullptr || layers_out == nullptr || time_out == nullptr)
+    return LYNX_ERR_INVALID_ARG;
+  const int P = pp->n_stages, L = pp->n_total_layers;
+  if (P < 1 || P > 64 || L < P || !(pp->t_fwd >= 0.0) || !(pp->t_bwd >= 0.0) || !(pp->static_per_layer >= 0.0))
+    return LYNX_ERR_INVALID_ARG;
+  {  // argument errors of the layer problem surface here, not as "does not fit"
+    lynx_policy_problem probe = *pp->layer;
+    probe.n_layer = 1;
+    probe.n_batch = 1;
+    probe.m_budget = INFINITY;
+    lynx_policy ignore;
+    const lynx_status st = lynx_policy_solve(&probe, &ignore);
+    if (st != LYNX_OK) return st;
+  }
+  int layers[64], trial[64];
+  StageEval cur[64], nxt[64];
+  for (int s = 0; s < P; ++s) layers[s] = L / P + (s < L % P ? 1 : 0);  // step (1)
+  for (int s = 0; s < P; ++s) {                                         // steps (2), (3)
+    cur[s] = eval_stage(*pp, s, layers[s]);
+    if (!cur[s].valid) return LYNX_ERR_OOM;
+  }
+  for (;;) {
+    int slow = 0, fast = 0;
+    for (int s = 1; s < P; ++s) {
+      if (cur[s].time > cur[slow].time) slow = s;
+      if (cur[s].time < cur[fast].time) fast = s;
+    }
+    if (slow == fast || layers[slow] <= 1) break;
+    for (int s = 0; s < P; ++s) { trial[s] = layers[s]; nxt[s] = cur[s]; }  // step (4)
+    trial[slow] -= 1;
+    trial[fast] += 1;
+    nxt[slow] = eval_stage(*pp, slow, trial[slow]);
+    nxt[fast] = eval_stage(*pp, fast, trial[fast]);
+    if (!nxt[slow].valid || !nxt[fast].valid) break;
+    double worst = 0.0;
+    for (int s = 0; s < P; ++s) worst = nxt[s].time > worst ? nxt[s].time : worst;
+    if (worst >= cur[slow].time - kEps) break;
+    for (int s = 0; s < P; ++s) { layers[s] = trial[s]; cur[s] = nxt[s]; }
+  }
+  for (int s = 0; s < P; ++s) {                                         // step (5)
+    layers_out[s] = layers[s];
+    time_out[s] = cur[s].time;
+    if (policies_out != nullptr) policies_out[s] = cur[s].policy;
+  }
+  return LYNX_OK;
+}
