@@ -39,6 +39,7 @@ constexpr int kBK = 32;        // K slab
 constexpr int kStages = 4;     // LDS ring depth
 constexpr int kThreads = 256;  // 4 wavefronts
 constexpr int kWaves = kThreads / kWave;
+constexpr double kPairCutFraction = 0.9;  // see plan_pair
 
 struct MfmaGemmArgs {
   const bf16_t* A; long long lda;
@@ -423,19 +424,37 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   gemm_tile<A_KMAJOR, B_KMAJOR, BM, BN>(g, blockIdx.x, blockIdx.y);
 }
 
+// An output whose width is an odd multiple of 128: 256 x 256 tiles over the columns that
+// whole tiles cover, and one column of 256 x 128 tiles (`edge`: the same product on the last
+// 128 columns) behind them in the same launch, where they fill the last round of workgroups.
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ void __launch_bounds__(kThreads)
+gemm_mfma_edge_kernel(MfmaGemmArgs body, MfmaGemmArgs edge, int n_body) {
+  if (static_cast<int>(blockIdx.x) < n_body) gemm_tile<A_KMAJOR, B_KMAJOR, 256, 256>(body, blockIdx.x, 0);
+  else gemm_tile<A_KMAJOR, B_KMAJOR, 256, 128>(edge, blockIdx.x - n_body, 0);
+}
+
 // The two products of a linear layer's backward in one launch: the weight gradient
 // (both operands MN-major, long contraction over the tokens) takes the first n_w
 // workgroups, the input gradient (weight MN-major) the rest.  Sharing a launch lets
 // the second product's tiles fill the compute units the first leaves idle in its
-// last, partial round.
-template <int DBM, int DBN, int WBM, int WBN>
+// last, partial round.  When one side of the weight gradient is an odd multiple of 128,
+// its 256 x 256 tiles cover all but the last 128 rows (or columns) and `wedge`, the same
+// product on that strip with EBM x EBN tiles, takes the n_e workgroups after them.
+template <int DBM, int DBN, int WBM, int WBN, int EBM, int EBN>
 __global__ void __launch_bounds__(kThreads)
-gemm_mfma_pair_kernel(MfmaGemmArgs wgrad, MfmaGemmArgs dgrad, int n_w) {
-  if (static_cast<int>(blockIdx.x) < n_w) {
-    if (wgrad.k_splits > 1) gemm_tile<false, false, WBM, WBN, true>(wgrad, blockIdx.x, 0);
-    else gemm_tile<false, false, WBM, WBN>(wgrad, blockIdx.x, 0);
+gemm_mfma_pair_kernel(MfmaGemmArgs wgrad, MfmaGemmArgs wedge, MfmaGemmArgs dgrad, int n_w, int n_e) {
+  const int x = static_cast<int>(blockIdx.x);
+  if (x < n_w) {
+    if (wgrad.k_splits > 1) gemm_tile<false, false, WBM, WBN, true>(wgrad, x, 0);
+    else gemm_tile<false, false, WBM, WBN>(wgrad, x, 0);
+  } else if (EBM != 0 && x < n_w + n_e) {
+    if constexpr (EBM != 0) {
+      if (wedge.k_splits > 1) gemm_tile<false, false, EBM, EBN, true>(wedge, x - n_w, 0);
+      else gemm_tile<false, false, EBM, EBN>(wedge, x - n_w, 0);
+    }
   } else
-    gemm_tile<true, false, DBM, DBN>(dgrad, blockIdx.x - n_w, 0);
+    gemm_tile<true, false, DBM, DBN>(dgrad, x - n_w - n_e, 0);
 }
 
 // C[m][n] = round(sum over the K ranges, in range order, of partial[split][m][n]).
@@ -478,6 +497,32 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <bool AK, bool BK_>
+hipError_t launch_edge(const MfmaGemmArgs& a, hipStream_t st) {
+  constexpr size_t smem = static_cast<size_t>(kStages) * (256 + 256) * kBK * sizeof(bf16_t);
+  auto kern = gemm_mfma_edge_kernel<AK, BK_>;
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(smem));
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  MfmaGemmArgs body = a, edge = a;
+  const int n_body_cols = a.N - 128;
+  body.N = n_body_cols;
+  body.tiles_m = a.M / 256; body.tiles_n = n_body_cols / 256;
+  edge.N = 128;
+  edge.tiles_m = a.M / 256; edge.tiles_n = 1;
+  edge.B = a.B + (BK_ ? static_cast<long long>(n_body_cols) * a.ldb : static_cast<long long>(n_body_cols));
+  edge.C = a.C + n_body_cols;
+  if (a.bias != nullptr) edge.bias = a.bias + n_body_cols;
+  const int n_body = body.tiles_m * body.tiles_n;
+  hipLaunchKernelGGL(kern, dim3(n_body + edge.tiles_m), dim3(kThreads), smem, st, body, edge, n_body);
+  return hipGetLastError();
+}
+
 // Tile shape: the largest tile that divides the output, unless a smaller one
 // fills the 256 compute units markedly better (fewer idle units in the last
 // round of workgroups).
@@ -492,6 +537,8 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
     a.tiles_n = a.N / 128;
     return launch<AK, BK_, 128, 128>(a, st);
   }
+  if (a.nz == 1 && a.M % 256 == 0 && a.N % 256 == 128 && (a.M / 256) * (a.N / 256 + 1) >= 128)
+    return launch_edge<AK, BK_>(a, st);
   struct Cand { int bm, bn; float weight; };
   static const Cand cands[4] = {{256, 256, 1.0f}, {256, 128, 0.8f}, {128, 256, 0.8f}, {128, 128, 0.6f}};
   int best = -1;
@@ -514,19 +561,55 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
   }
 }
 
-// Largest tile that divides the output (pair launches share their tail, so there is
-// no reason to shrink tiles for occupancy).
-bool pick_tile(const MfmaGemmArgs& a, int* bm, int* bn) {
-  *bm = a.M % 256 == 0 ? 256 : 128;
-  *bn = a.N % 256 == 0 ? 256 : 128;
-  return a.M % *bm == 0 && a.N % *bn == 0;
+// How a pair is launched.  Tiles: the largest that divides the output (pair launches
+// share their tail, so there is no reason to shrink tiles for occupancy); a weight gradient
+// with one side an odd multiple of 128 and at least half a round of whole tiles gets
+// 256 x 256 tiles plus an edge strip.  K ranges (1 or 2) of the weight gradient: its tiles
+// contract over all tokens and are few; when one of them lasts longer than nine tenths
+// of the launch's ideal duration, the compute units that have finished the input gradient
+// wait for it, and halving it pays for the extra pass over the fp32 partial sums (measured:
+// 10-30 % on the attention-projection shapes; finer cuts and cuts of the wide layers lose
+// to that pass).  Durations in slab units: 1 per slab for a 256 x 256 tile, about 0.55 for
+// the narrower ones.
+struct PairPlan {
+  int dbm, dbn;      // input-gradient tile
+  int wbm, wbn;      // weight-gradient tile
+  int edge;          // 0 none, 1 last 128 rows (128 x 256 tiles), 2 last 128 columns (256 x 128)
+  int k_splits;
+};
+
+PairPlan plan_pair(int wM, int wN, int wK, int dM, int dN, int dK) {
+  PairPlan p{};
+  p.dbm = dM % 256 == 0 ? 256 : 128;
+  p.dbn = dN % 256 == 0 ? 256 : 128;
+  p.wbm = wM % 256 == 0 ? 256 : 128;
+  p.wbn = wN % 256 == 0 ? 256 : 128;
+  if (wM % 256 == 128 && wN % 256 == 0 && (wM / 256) * (wN / 256) >= 128) { p.edge = 1; p.wbm = 256; }
+  else if (wN % 256 == 128 && wM % 256 == 0 && (wM / 256) * (wN / 256) >= 128) { p.edge = 2; p.wbn = 256; }
+  auto cost = [](int bm, int bn) { return (bm == 256 && bn == 256) ? 1.0 : 0.55; };
+  const double slabs_w = wK / kBK, slabs_d = dK / kBK;
+  double work_w, longest;
+  if (p.edge == 0) {
+    work_w = static_cast<double>(wM / p.wbm) * (wN / p.wbn) * slabs_w * cost(p.wbm, p.wbn);
+    longest = slabs_w * cost(p.wbm, p.wbn);
+  } else {
+    const double body = static_cast<double>(wM / 256) * (wN / 256);
+    const double strip = p.edge == 1 ? wN / 256 : wM / 256;
+    work_w = (body + strip * 0.55) * slabs_w;
+    longest = slabs_w;
+  }
+  const double work_d = static_cast<double>(dM / p.dbm) * (dN / p.dbn) * slabs_d * cost(p.dbm, p.dbn);
+  const double ideal = (work_w + work_d) / 256.0;
+  const bool cut = wK % (2 * kBK) == 0 && wK >= 2048 && longest > kPairCutFraction * ideal;
+  p.k_splits = cut ? 2 : 1;
+  return p;
 }
 
-template <int DBM, int DBN, int WBM, int WBN>
-hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, hipStream_t st) {
+template <int DBM, int DBN, int WBM, int WBN, int EBM, int EBN>
+hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, const PairPlan& plan, hipStream_t st) {
   constexpr int dsum = DBM + DBN, wsum = WBM + WBN;
   constexpr size_t smem = static_cast<size_t>(kStages) * (dsum > wsum ? dsum : wsum) * kBK * sizeof(bf16_t);
-  auto kern = gemm_mfma_pair_kernel<DBM, DBN, WBM, WBN>;
+  auto kern = gemm_mfma_pair_kernel<DBM, DBN, WBM, WBN, EBM, EBN>;
   static bool configured = false;
   if (!configured) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -535,36 +618,42 @@ hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, hipStream_t st) {
     if (e != hipSuccess) return e;
     configured = true;
   }
+  // the edge strip: the same product restricted to the last 128 rows or columns of dW
+  MfmaGemmArgs e = w;
+  int n_e = 0;
+  if (EBM != 0) {
+    if (plan.edge == 1) {
+      const int body_rows = w.M - 128;
+      e.A = w.A + body_rows;  // A is MN-major: column m of the stored [K, M] array
+      e.C = w.C + static_cast<long long>(body_rows) * w.ldc;
+      e.M = 128;
+      w.M = body_rows;
+    } else {
+      const int body_cols = w.N - 128;
+      e.B = w.B + body_cols;
+      e.C = w.C + body_cols;
+      e.N = 128;
+      w.N = body_cols;
+    }
+    if (w.k_splits > 1) e.partial = w.partial + static_cast<long long>(w.k_splits) * w.M * w.N;
+    e.tiles_m = e.M / EBM; e.tiles_n = e.N / EBN;
+    n_e = e.tiles_m * e.tiles_n * e.k_splits;
+  }
   w.tiles_m = w.M / WBM; w.tiles_n = w.N / WBN;
   d.tiles_m = d.M / DBM; d.tiles_n = d.N / DBN;
   const int n_w = w.tiles_m * w.tiles_n * w.k_splits;
-  hipLaunchKernelGGL(kern, dim3(n_w + d.tiles_m * d.tiles_n), dim3(kThreads), smem, st, w, d, n_w);
+  hipLaunchKernelGGL(kern, dim3(n_w + n_e + d.tiles_m * d.tiles_n), dim3(kThreads), smem, st, w, e, d, n_w, n_e);
   if (w.k_splits > 1) {
     const long long vecs = static_cast<long long>(w.M) * (w.N / 8);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>((vecs + 255) / 256)), dim3(256), 0, st,
                        w.partial, w.C, w.M, w.N, w.ldc, w.k_splits);
+    if (EBM != 0) {
+      const long long evecs = static_cast<long long>(e.M) * (e.N / 8);
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>((evecs + 255) / 256)), dim3(256), 0, st,
+                         e.partial, e.C, e.M, e.N, e.ldc, e.k_splits);
+    }
   }
   return hipGetLastError();
-}
-
-// How many K ranges (1 or 2) the weight gradient of a pair is cut into.  Its tiles contract
-// over all tokens and are few; when one of them lasts longer than three quarters of the
-// launch's ideal duration, the compute units that have finished the input gradient wait for
-// it, and halving it pays for the extra pass over the fp32 partial sums (measured: 10-30 %
-// on the attention-projection shapes; finer cuts and cuts of the wide layers lose to that
-// pass).  Durations in slab units: 1 per slab for a 256 x 256 tile, about 0.55 for the
-// narrower ones.
-int pair_k_splits(int wM, int wN, int wK, int dM, int dN, int dK) {
-  auto tiles = [](int M, int N, double* cost) {
-    const int bm = M % 256 == 0 ? 256 : 128, bn = N % 256 == 0 ? 256 : 128;
-    *cost = (bm == 256 && bn == 256) ? 1.0 : 0.55;
-    return static_cast<double>(M / bm) * (N / bn);
-  };
-  double cw, cd;
-  const double nw = tiles(wM, wN, &cw), nd = tiles(dM, dN, &cd);
-  const double ideal = (nw * (wK / kBK) * cw + nd * (dK / kBK) * cd) / 256.0;
-  const bool cut = wK % (2 * kBK) == 0 && wK >= 2048 && (wK / kBK) * cw > 0.75 * ideal;
-  return cut ? 2 : 1;
 }
 
 MfmaGemmArgs make_args(const GemmDesc& d) {
@@ -615,41 +704,40 @@ bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& 
   if (dgrad.causal != kCausalNone || wgrad.causal != kCausalNone) return false;
   if (!(dgrad.a_sk == 1 && dgrad.b_sn == 1 && dgrad.b_sk != 1)) return false;  // A K-major, B MN-major
   if (!(wgrad.a_sm == 1 && wgrad.a_sk != 1 && wgrad.b_sn == 1 && wgrad.b_sk != 1)) return false;
-  int bm, bn;
-  const MfmaGemmArgs d = make_args(dgrad), w = make_args(wgrad);
-  if (!pick_tile(d, &bm, &bn) || bm != 256) return false;
-  if (!pick_tile(w, &bm, &bn) || (bm == 128 && bn == 128)) return false;
+  const PairPlan p = plan_pair(wgrad.M, wgrad.N, wgrad.K, dgrad.M, dgrad.N, dgrad.K);
+  if (p.dbm != 256) return false;
+  if (p.wbm == 128 && p.wbn == 128) return false;
   return true;
 }
 
 size_t gemm_pair_scratch_bytes(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad) {
   if (dtype != 1) return 0;
-  const int s = pair_k_splits(wgrad.M, wgrad.N, wgrad.K, dgrad.M, dgrad.N, dgrad.K);
-  return s > 1 ? static_cast<size_t>(s) * wgrad.M * wgrad.N * sizeof(float) : 0;
+  const PairPlan p = plan_pair(wgrad.M, wgrad.N, wgrad.K, dgrad.M, dgrad.N, dgrad.K);
+  return p.k_splits > 1 ? static_cast<size_t>(p.k_splits) * wgrad.M * wgrad.N * sizeof(float) : 0;
 }
 
 hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, float* scratch, size_t scratch_bytes,
                           hipStream_t st) {
   const MfmaGemmArgs d = make_args(dgrad);
   MfmaGemmArgs w = make_args(wgrad);
-  const int splits = pair_k_splits(w.M, w.N, w.K, d.M, d.N, d.K);
-  if (splits > 1 && scratch != nullptr && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0 &&
-      scratch_bytes >= static_cast<size_t>(splits) * w.M * w.N * sizeof(float)) {
-    w.k_splits = splits;
+  const PairPlan p = plan_pair(w.M, w.N, w.K, d.M, d.N, d.K);
+  if (p.k_splits > 1 && scratch != nullptr && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0 &&
+      scratch_bytes >= static_cast<size_t>(p.k_splits) * w.M * w.N * sizeof(float)) {
+    w.k_splits = p.k_splits;
     w.partial = scratch;
   }
-  int dbm, dbn, wbm, wbn;
-  pick_tile(d, &dbm, &dbn);
-  pick_tile(w, &wbm, &wbn);
-  const int wsel = wbm == 256 ? (wbn == 256 ? 0 : 1) : 2;
-  if (dbn == 256) {
-    if (wsel == 0) return launch_pair<256, 256, 256, 256>(w, d, st);
-    if (wsel == 1) return launch_pair<256, 256, 256, 128>(w, d, st);
-    return launch_pair<256, 256, 128, 256>(w, d, st);
+  if (p.dbn == 256) {
+    if (p.edge == 1) return launch_pair<256, 256, 256, 256, 128, 256>(w, d, p, st);
+    if (p.edge == 2) return launch_pair<256, 256, 256, 256, 256, 128>(w, d, p, st);
+    if (p.wbm == 256 && p.wbn == 256) return launch_pair<256, 256, 256, 256, 0, 0>(w, d, p, st);
+    if (p.wbm == 256) return launch_pair<256, 256, 256, 128, 0, 0>(w, d, p, st);
+    return launch_pair<256, 256, 128, 256, 0, 0>(w, d, p, st);
   }
-  if (wsel == 0) return launch_pair<256, 128, 256, 256>(w, d, st);
-  if (wsel == 1) return launch_pair<256, 128, 256, 128>(w, d, st);
-  return launch_pair<256, 128, 128, 256>(w, d, st);
+  if (p.edge == 1) return launch_pair<256, 128, 256, 256, 128, 256>(w, d, p, st);
+  if (p.edge == 2) return launch_pair<256, 128, 256, 256, 256, 128>(w, d, p, st);
+  if (p.wbm == 256 && p.wbn == 256) return launch_pair<256, 128, 256, 256, 0, 0>(w, d, p, st);
+  if (p.wbm == 256) return launch_pair<256, 128, 256, 128, 0, 0>(w, d, p, st);
+  return launch_pair<256, 128, 128, 256, 0, 0>(w, d, p, st);
 }
 
 }  // namespace lynx
