@@ -4,6 +4,7 @@
 // consecutive vectors.  Column sums are two fixed-order stages (per row-block
 // partials, then a serial sum over row-blocks), so results are deterministic.
 #include "dropout_host.h"
+#include "pointwise_math.h"
 #include "reduce_partials.h"
 
 namespace lynx {
@@ -11,23 +12,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kRowsPerBlock = 32;  // rows folded into one column-sum partial
-
-// tanh-form GeLU (operator 11) and its derivative.
-constexpr float kKappa = 0.7978845608028654f;  // sqrt(2/pi)
-constexpr float kGeluC = 0.044715f;
-
-__device__ __forceinline__ float tanh_fast(float x) {
-  // 1 - 2/(1+e^{2x}); saturates correctly at both ends
-  return 1.0f - __fdividef(2.0f, 1.0f + __expf(2.0f * x));
-}
-__device__ __forceinline__ float gelu_f(float u) {
-  const float th = tanh_fast(kKappa * (u + kGeluC * u * u * u));
-  return 0.5f * u * (1.0f + th);
-}
-__device__ __forceinline__ float gelu_grad_f(float u) {
-  const float th = tanh_fast(kKappa * (u + kGeluC * u * u * u));
-  return 0.5f * (1.0f + th) + 0.5f * u * (1.0f - th * th) * kKappa * (1.0f + 3.0f * kGeluC * u * u);
-}
 
 template <typename T>
 __global__ void __launch_bounds__(kThreads) gelu_fwd_kernel(const T* __restrict__ u,
@@ -50,8 +34,7 @@ struct GeluBwdOp {  // du = dg * gelu'(u)
   static constexpr bool kStores = true;
   __device__ __forceinline__ void apply(const float (&a)[8], const float (&b)[8], size_t,
                                         float (&out)[8]) const {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = round_to_storage(a[i] * gelu_grad_f(b[i]), static_cast<T*>(nullptr));
+    gelu_bwd8<T>(a, b, out);
   }
 };
 
@@ -159,12 +142,9 @@ bias_dropout_add_kernel(const T* __restrict__ in, const T* __restrict__ bias,
   load8(in + off, a);
   load8(bias + c, b);
   load8(res + off, r);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) a[i] += b[i];
-  dropout_apply8(key, v, a);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) r[i] += a[i];
-  store8(out + off, r);
+  float o[8];
+  bias_dropout_add8(a, b, r, key, v, o);
+  store8(out + off, o);
 }
 
 __global__ void __launch_bounds__(kThreads)

@@ -24,8 +24,9 @@
 // tile through LDS and stores whole rows, 16 bytes per lane.
 #include <type_traits>
 
-#include "device_common.h"
-#include "kernels.h"
+#include "dropout_host.h"
+#include "pointwise_math.h"
+#include "reduce_partials.h"
 
 namespace lynx {
 namespace {
@@ -56,6 +57,16 @@ struct MfmaGemmArgs {
   // ranges and leaves its fp32 sums in partial[split][M][N] instead of rounding into C
   int k_splits;
   float* partial;
+  // fused epilogue (GemmEpilogueKind).  aux / vec / plain are indexed with the absolute
+  // column col0 + n, so a launch that covers a column range of the output (edge strips)
+  // passes them unchanged; row_len is the full row length (the dropout element index).
+  int epi;
+  int col0, row_len;
+  const bf16_t* aux; long long aux_ld;
+  const bf16_t* vec;
+  bf16_t* plain;
+  float* colsum_partial;
+  DropoutKey key;
 };
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -409,13 +420,62 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
       }
     }
   constexpr int kRowsPerStore = kWave / kRowChunks;
+  constexpr int kIters = WM / kRowsPerStore;
   bf16_t* cw = Cbase + static_cast<long long>(m0 + wm0) * g.ldc + n0 + wn0;
+  const int lr = lane / kRowChunks, lc = lane % kRowChunks;
+  if (g.epi == kEpiNone) {
 #pragma unroll
-  for (int t = 0; t < WM / kRowsPerStore; ++t) {
-    const int r = t * kRowsPerStore + lane / kRowChunks;
-    const int lc = lane % kRowChunks;
-    const uint4 v = *reinterpret_cast<const uint4*>(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3));
-    *reinterpret_cast<uint4*>(cw + static_cast<long long>(r) * g.ldc + lc * 8) = v;
+    for (int t = 0; t < kIters; ++t) {
+      const int r = t * kRowsPerStore + lr;
+      const uint4 v = *reinterpret_cast<const uint4*>(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3));
+      *reinterpret_cast<uint4*>(cw + static_cast<long long>(r) * g.ldc + lc * 8) = v;
+    }
+    return;
+  }
+  // Fused epilogues: the lane that stores 8 consecutive outputs of a row first combines
+  // them with the same 8 elements of `aux`, loaded a batch of rows ahead.
+  constexpr int kBatch = 8;
+  static_assert(kIters % kBatch == 0, "epilogue batches");
+  const long long row0 = m0 + wm0;
+  const int col = g.col0 + n0 + wn0 + lc * 8;  // absolute column
+  const bf16_t* auxp = g.aux + row0 * g.aux_ld + col;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (g.epi == kEpiBiasDropoutAdd) load8(g.vec + col, bv);
+  float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int t0 = 0; t0 < kIters; t0 += kBatch) {
+    Raw8<bf16_t> ra[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k)
+      load_raw(auxp + static_cast<long long>((t0 + k) * kRowsPerStore + lr) * g.aux_ld, ra[k]);
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) {
+      const int r = (t0 + k) * kRowsPerStore + lr;
+      Raw8<bf16_t> pv;
+      pv.v = *reinterpret_cast<const uint4*>(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3));
+      float prod[8], x[8], o[8];
+      unpack(pv, prod);
+      unpack(ra[k], x);
+      if (g.epi == kEpiBiasDropoutAdd) {
+        if (g.plain != nullptr)
+          *reinterpret_cast<uint4*>(g.plain + (row0 + r) * g.ldc + col) = pv.v;
+        const uint64_t elem = static_cast<uint64_t>(row0 + r) * static_cast<uint64_t>(g.row_len) + col;
+        bias_dropout_add8(prod, bv, x, g.key, elem >> 3, o);
+      } else {
+        gelu_bwd8<bf16_t>(prod, x, o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) colacc[i] += o[i];
+      }
+      store8(cw + static_cast<long long>(r) * g.ldc + lc * 8, o);
+    }
+  }
+  if (g.epi == kEpiGeluBwd) {
+    // column sums of this wavefront's WM rows: lanes with the same lc hold different rows
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int o = kRowChunks; o < kWave; o <<= 1) colacc[i] += __shfl_xor(colacc[i], o, kWave);
+    if (lane < kRowChunks)
+      store8(g.colsum_partial + (row0 / WM) * g.row_len + col, colacc);
   }
 }
 
@@ -518,6 +578,7 @@ hipError_t launch_edge(const MfmaGemmArgs& a, hipStream_t st) {
   edge.B = a.B + (BK_ ? static_cast<long long>(n_body_cols) * a.ldb : static_cast<long long>(n_body_cols));
   edge.C = a.C + n_body_cols;
   if (a.bias != nullptr) edge.bias = a.bias + n_body_cols;
+  edge.col0 = a.col0 + n_body_cols;
   const int n_body = body.tiles_m * body.tiles_n;
   hipLaunchKernelGGL(kern, dim3(n_body + edge.tiles_m), dim3(kThreads), smem, st, body, edge, n_body);
   return hipGetLastError();
@@ -668,6 +729,15 @@ MfmaGemmArgs make_args(const GemmDesc& d) {
   a.c_z1 = d.c_sz1; a.c_z2 = d.c_sz2;
   a.nz = d.nz1 * d.nz2; a.nz2 = d.nz2; a.causal = d.causal;
   a.k_splits = 1; a.partial = nullptr;
+  a.epi = d.epi.kind;
+  a.col0 = 0; a.row_len = d.N;
+  if (d.epi.kind != kEpiNone) {
+    a.aux = static_cast<const bf16_t*>(d.epi.aux); a.aux_ld = d.epi.aux_ld;
+    a.vec = static_cast<const bf16_t*>(d.epi.vec);
+    a.plain = static_cast<bf16_t*>(d.epi.plain);
+    a.colsum_partial = d.epi.colsum_partial;
+    if (d.epi.kind == kEpiBiasDropoutAdd) a.key = make_dropout_key(d.epi.dp, d.epi.site);
+  }
   return a;
 }
 
@@ -686,10 +756,28 @@ bool gemm_mfma_supported(int dtype, const GemmDesc& d) {
   if ((reinterpret_cast<uintptr_t>(d.A) | reinterpret_cast<uintptr_t>(d.B)) & 15) return false;
   if (reinterpret_cast<uintptr_t>(d.C) & 15) return false;
   if (d.bias != nullptr && (reinterpret_cast<uintptr_t>(d.bias) & 7)) return false;
+  if (d.epi.kind != kEpiNone) {
+    if (d.epi.kind != kEpiBiasDropoutAdd && d.epi.kind != kEpiGeluBwd) return false;
+    if (d.causal != kCausalNone || d.nz1 * d.nz2 != 1 || d.bias != nullptr) return false;
+    if (d.epi.aux == nullptr || (reinterpret_cast<uintptr_t>(d.epi.aux) & 15) || d.epi.aux_ld % 8) return false;
+    if (d.epi.kind == kEpiBiasDropoutAdd) {
+      if (d.epi.vec == nullptr || (reinterpret_cast<uintptr_t>(d.epi.vec) & 15)) return false;
+      if (d.epi.plain != nullptr && (reinterpret_cast<uintptr_t>(d.epi.plain) & 15)) return false;
+    } else {
+      // column partials are laid out per 128 rows: 256-row tiles only, which the pair launch uses
+      if (d.M % 256 || d.epi.colsum_partial == nullptr || d.epi.colsum_out == nullptr) return false;
+      if (reinterpret_cast<uintptr_t>(d.epi.colsum_partial) & 15) return false;
+    }
+  }
   return true;
 }
 
+size_t gemm_colsum_partial_bytes(int M, int N) {
+  return static_cast<size_t>((M + 127) / 128) * static_cast<size_t>(N) * sizeof(float);
+}
+
 hipError_t gemm_mfma(const GemmDesc& d, hipStream_t st) {
+  if (d.epi.kind == kEpiGeluBwd) return hipErrorInvalidValue;  // needs the pair launch's 256-row tiles
   const MfmaGemmArgs a = make_args(d);
   const bool a_k = d.a_sk == 1, b_k = d.b_sk == 1;
   if (a_k && b_k) return launch_tiles<true, true>(a, st);
@@ -704,6 +792,7 @@ bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& 
   if (dgrad.causal != kCausalNone || wgrad.causal != kCausalNone) return false;
   if (!(dgrad.a_sk == 1 && dgrad.b_sn == 1 && dgrad.b_sk != 1)) return false;  // A K-major, B MN-major
   if (!(wgrad.a_sm == 1 && wgrad.a_sk != 1 && wgrad.b_sn == 1 && wgrad.b_sk != 1)) return false;
+  if (wgrad.epi.kind != kEpiNone || dgrad.epi.kind == kEpiBiasDropoutAdd) return false;
   const PairPlan p = plan_pair(wgrad.M, wgrad.N, wgrad.K, dgrad.M, dgrad.N, dgrad.K);
   if (p.dbm != 256) return false;
   if (p.wbm == 128 && p.wbn == 128) return false;
@@ -726,18 +815,29 @@ hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, float* s
     w.k_splits = p.k_splits;
     w.partial = scratch;
   }
-  if (p.dbn == 256) {
-    if (p.edge == 1) return launch_pair<256, 256, 256, 256, 128, 256>(w, d, p, st);
-    if (p.edge == 2) return launch_pair<256, 256, 256, 256, 256, 128>(w, d, p, st);
-    if (p.wbm == 256 && p.wbn == 256) return launch_pair<256, 256, 256, 256, 0, 0>(w, d, p, st);
-    if (p.wbm == 256) return launch_pair<256, 256, 256, 128, 0, 0>(w, d, p, st);
-    return launch_pair<256, 256, 128, 256, 0, 0>(w, d, p, st);
+  auto run = [&]() -> hipError_t {
+    if (p.dbn == 256) {
+      if (p.edge == 1) return launch_pair<256, 256, 256, 256, 128, 256>(w, d, p, st);
+      if (p.edge == 2) return launch_pair<256, 256, 256, 256, 256, 128>(w, d, p, st);
+      if (p.wbm == 256 && p.wbn == 256) return launch_pair<256, 256, 256, 256, 0, 0>(w, d, p, st);
+      if (p.wbm == 256) return launch_pair<256, 256, 256, 128, 0, 0>(w, d, p, st);
+      return launch_pair<256, 256, 128, 256, 0, 0>(w, d, p, st);
+    }
+    if (p.edge == 1) return launch_pair<256, 128, 256, 256, 128, 256>(w, d, p, st);
+    if (p.edge == 2) return launch_pair<256, 128, 256, 256, 256, 128>(w, d, p, st);
+    if (p.wbm == 256 && p.wbn == 256) return launch_pair<256, 128, 256, 256, 0, 0>(w, d, p, st);
+    if (p.wbm == 256) return launch_pair<256, 128, 256, 128, 0, 0>(w, d, p, st);
+    return launch_pair<256, 128, 128, 256, 0, 0>(w, d, p, st);
+  };
+  const hipError_t e = run();
+  if (e != hipSuccess) return e;
+  if (dgrad.epi.kind == kEpiGeluBwd) {
+    // second, fixed-order stage of the bias gradient: one partial row per 128 output rows
+    launch_reduce_partials<bf16_t>(dgrad.epi.colsum_partial, static_cast<bf16_t*>(dgrad.epi.colsum_out), nullptr,
+                                   nullptr, dgrad.M / 128, dgrad.N, st);
+    return hipGetLastError();
   }
-  if (p.edge == 1) return launch_pair<256, 128, 256, 256, 128, 256>(w, d, p, st);
-  if (p.edge == 2) return launch_pair<256, 128, 256, 256, 256, 128>(w, d, p, st);
-  if (p.wbm == 256 && p.wbn == 256) return launch_pair<256, 128, 256, 256, 0, 0>(w, d, p, st);
-  if (p.wbm == 256) return launch_pair<256, 128, 256, 128, 0, 0>(w, d, p, st);
-  return launch_pair<256, 128, 128, 256, 0, 0>(w, d, p, st);
+  return hipSuccess;
 }
 
 }  // namespace lynx

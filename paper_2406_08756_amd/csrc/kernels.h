@@ -81,6 +81,32 @@ enum CausalMode : int {
   kCausalKGeM = 3       // contraction restricted to k >= m
 };
 
+// Elementwise work a matrix-core product can absorb into the pass that stores its output
+// tile, so the operator that would read the product back never runs as a kernel of its
+// own.  P = the product rounded to storage, exactly what an unfused launch would store.
+enum GemmEpilogueKind : int {
+  kEpiNone = 0,
+  // bias + dropout + residual (operators 8, 13): C = aux + keep (P + vec) c at dropout site
+  // `site`, element index m * N + n; if `plain` is not null P is stored there as well (row
+  // stride = c_sm).  Bit-identical to bias_dropout_add_fwd run on a stored P.
+  kEpiBiasDropoutAdd = 1,
+  // GeLU backward (input gradient of FC2 only, inside gemm_pair): C = P gelu'(aux) and
+  // colsum_out[n] = sum_m C[m, n] (the FC1 bias gradient), reduced in two fixed-order stages
+  // through `colsum_partial` (gemm_colsum_partial_bytes).
+  kEpiGeluBwd = 2
+};
+struct GemmEpilogue {
+  int kind;
+  const void* aux;        // [M, N], row stride aux_ld: the residual (1) or U (2)
+  long long aux_ld;
+  const void* vec;        // (1) bias[N]
+  void* plain;            // (1) nullable
+  int site;               // (1)
+  DropoutParams dp;       // (1)
+  float* colsum_partial;  // (2)
+  void* colsum_out;       // (2) [N], storage dtype
+};
+
 // C[z][m, n] = sum_k A[z][m, k] * B[z][k, n] (+ bias[n]), z = (z1, z2) a
 // two-level batch.  Element strides are explicit, so any operand may be a
 // transposed or column-sliced view.  Accumulation is fp32 in a fixed order.
@@ -92,6 +118,7 @@ struct GemmDesc {
   const void* bias;                        // nullable, length N, same dtype
   int nz1, nz2;
   int causal;                              // CausalMode
+  GemmEpilogue epi;                        // kind 0 (none) unless the matrix-core path is used
 };
 hipError_t gemm(int dtype, const GemmDesc& d, hipStream_t st);          // picks a kernel
 hipError_t gemm_generic(int dtype, const GemmDesc& d, hipStream_t st);  // any shape, vector ALUs
@@ -105,6 +132,7 @@ hipError_t gemm_pair(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad, fl
                      size_t scratch_bytes, hipStream_t st);
 size_t gemm_pair_scratch_bytes(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad);  // shapes only
 bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& wgrad);
+size_t gemm_colsum_partial_bytes(int M, int N);  // kEpiGeluBwd
 hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, float* scratch, size_t scratch_bytes,
                           hipStream_t st);
 

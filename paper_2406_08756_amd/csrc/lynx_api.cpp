@@ -365,17 +365,63 @@ lynx_status run_op(Ctx& cx, int i, bool fuse_dropout = false, bool write_p = tru
   return LYNX_OK;
 }
 
+// OP7 + OP8 (or OP12 + OP13) as one launch: the product of operator `lin` is rounded as
+// it would be stored, and the store pass of the matrix-product kernel applies bias,
+// dropout and residual to it, so the operator that would read it back never runs.  The
+// product itself is kept (written as well) only if the policy retains it.  Same bits as the
+// two operators run one after the other.
+GemmDesc fused_linear_desc(Ctx& cx, int lin, bool keep_product) {
+  lynx_layer_s* L = cx.L;
+  const Dims& D = L->D;
+  const lynx_params& w = L->params;
+  const bool first = lin == 7;
+  GemmDesc g = first ? linear_fwd(act_ptr(cx, 6), w.wo, nullptr, nullptr, D.T, D.h, D.p)
+                     : linear_fwd(act_ptr(cx, 11), w.w2, nullptr, nullptr, D.T, D.h, D.f);
+  g.C = cx.bk->live[lin + 1] ? act_ptr(cx, lin + 1) : nullptr;
+  g.epi.kind = lynx::kEpiBiasDropoutAdd;
+  g.epi.aux = first ? act_ptr(cx, 0) : act_ptr(cx, 8);
+  g.epi.aux_ld = D.h;
+  g.epi.vec = first ? w.bo : w.b2;
+  g.epi.plain = keep_product ? act_ptr(cx, lin) : nullptr;
+  g.epi.site = first ? 1 : 2;
+  g.epi.dp = dropout_params(L);
+  return g;
+}
+bool can_fuse_linear(const lynx_layer_s* L, int lin) {
+  const Dims& D = L->D;
+  // shapes only (pointers are 256-byte aligned arena blocks or checked caller buffers)
+  GemmDesc g = linear_fwd(reinterpret_cast<const void*>(256), reinterpret_cast<const void*>(256), nullptr,
+                          reinterpret_cast<void*>(256), D.T, D.h, lin == 7 ? D.p : D.f);
+  g.epi.kind = lynx::kEpiBiasDropoutAdd;
+  g.epi.aux = reinterpret_cast<const void*>(256);
+  g.epi.aux_ld = D.h;
+  g.epi.vec = reinterpret_cast<const void*>(256);
+  return lynx::gemm_mfma_supported(D.dtype, g);
+}
+lynx_status run_fused_linear(Ctx& cx, int lin) {
+  const bool keep_product = (cx.bk->retain >> lin) & 1u;
+  if (keep_product) LYNX_TRY(alloc_act(cx, lin));
+  LYNX_TRY(alloc_act(cx, lin + 1));
+  LYNX_LAUNCH(cx, lin, lynx::gemm(cx.L->D.dtype, fused_linear_desc(cx, lin, keep_product), cx.st));
+  return LYNX_OK;
+}
+
 lynx_status forward_pass(Ctx& cx, uint32_t retain) {
   Book& bk = *cx.bk;
   bk.retain = (retain & 0x3FFFu) | kCallerOwned;
   bk.live[0] = true;
   for (int i = 1; i <= kNumOps; ++i) {
     if (i == 5) continue;  // emitted by OP4's kernel
-    if (i == 4)
+    int done = i;
+    if (i == 4) {
       LYNX_TRY(run_op(cx, 4, /*fuse_dropout=*/true, /*write_p=*/(bk.retain >> 4) & 1u));
-    else
+      done = 5;  // OP4's launch covers OP5
+    } else if ((i == 7 || i == 12) && can_fuse_linear(cx.L, i)) {
+      LYNX_TRY(run_fused_linear(cx, i));
+      done = ++i;  // the launch covers the bias + dropout + residual operator too
+    } else {
       LYNX_TRY(run_op(cx, i));
-    const int done = (i == 4) ? 5 : i;  // OP4's launch covers OP5
+    }
     for (int j = 1; j <= 12; ++j)
       if (bk.live[j] && kLastForwardUse[j] <= done && !((bk.retain >> j) & 1u)) free_act(cx, j);
   }
@@ -433,10 +479,15 @@ lynx_status recompute_pass(Ctx& cx, uint32_t segment) {
   }
   for (int i = 1; i <= kNumOps; ++i) {
     if (!((segment >> i) & 1u) || bk.live[i]) continue;
-    if (i == 4 && ((segment >> 5) & 1u) && !bk.live[5])
+    if (i == 4 && ((segment >> 5) & 1u) && !bk.live[5]) {
       LYNX_TRY(run_op(cx, 4, /*fuse_dropout=*/true));
-    else
+    } else if ((i == 7 || i == 12) && ((segment >> (i + 1)) & 1u) && !bk.live[i + 1] &&
+               can_fuse_linear(cx.L, i)) {
+      LYNX_TRY(run_fused_linear(cx, i));
+      ++i;
+    } else {
       LYNX_TRY(run_op(cx, i));
+    }
     release_stepping_stones(cx);
   }
   return LYNX_OK;
@@ -472,17 +523,38 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_TRY(alloc_temp(cx, th, &t_dv2));
   LYNX_LAUNCH(cx, kB13Dropout, lynx::dropout_bwd(dt, d_out, temp_ptr(cx, t_dv2), gr->b2, scr, D.T, D.h, 2,
                                     dropout_params(L), cx.st));
-  // B12: V2 = G W2^T
-  LYNX_TRY(alloc_temp(cx, tf, &t_dg));
-  LYNX_LAUNCH(cx, kB12Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_dg), D.T, D.h, D.f),
-                                                  linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T, D.h, D.f), scr, scratch_bytes, cx.st));
-  free_temp(cx, &t_dv2);
-  free_act(cx, 11);
-  // B11: G = gelu(U)
+  // B12: V2 = G W2^T, and B11: G = gelu(U).  When the matrix-core pair launch applies, the
+  // store pass of the input gradient multiplies by gelu'(U) and sums the columns (the FC1
+  // bias gradient), so dG is never written and the GeLU backward never runs as a kernel.
   LYNX_TRY(alloc_temp(cx, tf, &t_du));
-  LYNX_LAUNCH(cx, kB11Gelu, lynx::gelu_bwd(dt, temp_ptr(cx, t_dg), act_ptr(cx, 10), temp_ptr(cx, t_du),
-                                 gr->b1, scr, D.T, D.f, cx.st));
-  free_temp(cx, &t_dg);
+  {
+    GemmDesc dg = linear_dgrad(temp_ptr(cx, t_dv2), w.w2, temp_ptr(cx, t_du), D.T, D.h, D.f);
+    const GemmDesc wg = linear_wgrad(temp_ptr(cx, t_dv2), act_ptr(cx, 11), gr->w2, D.T, D.h, D.f);
+    Temp t_colsum;
+    LYNX_TRY(alloc_temp(cx, lynx::gemm_colsum_partial_bytes(D.T, D.f), &t_colsum));
+    dg.epi.kind = lynx::kEpiGeluBwd;
+    dg.epi.aux = act_ptr(cx, 10);
+    dg.epi.aux_ld = D.f;
+    dg.epi.colsum_partial = reinterpret_cast<float*>(temp_ptr(cx, t_colsum));
+    dg.epi.colsum_out = gr->b1;
+    if (lynx::gemm_mfma_pair_supported(dt, dg, wg)) {
+      LYNX_LAUNCH(cx, kB12Grads, lynx::gemm_mfma_pair(dg, wg, scr, scratch_bytes, cx.st));
+      free_temp(cx, &t_colsum);
+      free_temp(cx, &t_dv2);
+      free_act(cx, 11);
+    } else {
+      free_temp(cx, &t_colsum);
+      dg.epi = lynx::GemmEpilogue{};
+      LYNX_TRY(alloc_temp(cx, tf, &t_dg));
+      dg.C = temp_ptr(cx, t_dg);
+      LYNX_LAUNCH(cx, kB12Grads, lynx::gemm_pair(dt, dg, wg, scr, scratch_bytes, cx.st));
+      free_temp(cx, &t_dv2);
+      free_act(cx, 11);
+      LYNX_LAUNCH(cx, kB11Gelu, lynx::gelu_bwd(dt, temp_ptr(cx, t_dg), act_ptr(cx, 10), temp_ptr(cx, t_du),
+                                               gr->b1, scr, D.T, D.f, cx.st));
+      free_temp(cx, &t_dg);
+    }
+  }
   free_act(cx, 10);
   // B10: U = Y2 W1^T + b1
   LYNX_TRY(alloc_temp(cx, th, &t_dy2));
