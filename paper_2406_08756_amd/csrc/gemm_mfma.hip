@@ -33,6 +33,7 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4_t __attribute__((ext_vector_type(4)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
@@ -396,8 +397,32 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
       for (int q = 0; q < 4; ++q)
         braw[i][q] = *reinterpret_cast<const uint2*>(g.bias + n0 + wn0 + 32 * i + 8 * q + 4 * (lane >> 5));
   }
-  block_barrier();  // every wavefront is done with the ring (no load is in flight any more)
   constexpr int kRowChunks = WN / 8;
+  constexpr int kRowsPerStore = kWave / kRowChunks;
+  constexpr int kIters = WM / kRowsPerStore;
+  // (an opaque copy of the lane index: nothing derived from it can be computed, and kept
+  // in registers, ahead of the contraction loop)
+  int elane = lane;
+  asm volatile("" : "+v"(elane));
+  const int lr = elane / kRowChunks, lc = elane % kRowChunks;
+  const long long row0 = m0 + wm0;
+  const int col = g.col0 + n0 + wn0 + lc * 8;  // absolute column of this lane's 8 outputs
+  // Fused epilogues combine every 8 outputs with the same 8 elements of `aux`, fetched in
+  // batches of 8 per lane, two batches in flight; the first is requested here, so it
+  // arrives while the tile is rounded into LDS.
+  constexpr int kBatch = 8;
+  constexpr int kBatches = kIters / kBatch;
+  static_assert(kIters % kBatch == 0, "epilogue batches");
+  uintx4_t ra0[kBatch], ra1[kBatch];
+  const bf16_t* auxp = g.epi != kEpiNone ? g.aux + row0 * g.aux_ld + col : nullptr;
+  auto aux_load = [&](uintx4_t (&ra)[kBatch], int batch) {
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k)
+      ra[k] = *reinterpret_cast<const uintx4_t*>(
+          auxp + static_cast<long long>((batch * kBatch + k) * kRowsPerStore + lr) * g.aux_ld);
+  };
+  if (g.epi != kEpiNone) aux_load(ra0, 0);
+  block_barrier();  // every wavefront is done with the ring (no load is in flight any more)
   bf16_t* stage = smem + wave * (WM * WN);
 #pragma unroll
   for (int i = 0; i < TN; ++i)
@@ -419,10 +444,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
         *reinterpret_cast<uint2*>(stage + ml * WN + chunk * 8 + (nl & 7)) = o;
       }
     }
-  constexpr int kRowsPerStore = kWave / kRowChunks;
-  constexpr int kIters = WM / kRowsPerStore;
   bf16_t* cw = Cbase + static_cast<long long>(m0 + wm0) * g.ldc + n0 + wn0;
-  const int lr = lane / kRowChunks, lc = lane % kRowChunks;
   if (g.epi == kEpiNone) {
 #pragma unroll
     for (int t = 0; t < kIters; ++t) {
@@ -432,29 +454,19 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
     }
     return;
   }
-  // Fused epilogues: the lane that stores 8 consecutive outputs of a row first combines
-  // them with the same 8 elements of `aux`, loaded a batch of rows ahead.
-  constexpr int kBatch = 8;
-  static_assert(kIters % kBatch == 0, "epilogue batches");
-  const long long row0 = m0 + wm0;
-  const int col = g.col0 + n0 + wn0 + lc * 8;  // absolute column
-  const bf16_t* auxp = g.aux + row0 * g.aux_ld + col;
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (g.epi == kEpiBiasDropoutAdd) load8(g.vec + col, bv);
   float colacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int t0 = 0; t0 < kIters; t0 += kBatch) {
-    Raw8<bf16_t> ra[kBatch];
-#pragma unroll
-    for (int k = 0; k < kBatch; ++k)
-      load_raw(auxp + static_cast<long long>((t0 + k) * kRowsPerStore + lr) * g.aux_ld, ra[k]);
+  auto finish = [&](const uintx4_t (&ra)[kBatch], int batch) {
 #pragma unroll
     for (int k = 0; k < kBatch; ++k) {
-      const int r = (t0 + k) * kRowsPerStore + lr;
-      Raw8<bf16_t> pv;
+      const int r = (batch * kBatch + k) * kRowsPerStore + lr;
+      Raw8<bf16_t> pv, xv;
       pv.v = *reinterpret_cast<const uint4*>(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3));
+      xv.v = make_uint4(ra[k][0], ra[k][1], ra[k][2], ra[k][3]);
       float prod[8], x[8], o[8];
       unpack(pv, prod);
-      unpack(ra[k], x);
+      unpack(xv, x);
       if (g.epi == kEpiBiasDropoutAdd) {
         if (g.plain != nullptr)
           *reinterpret_cast<uint4*>(g.plain + (row0 + r) * g.ldc + col) = pv.v;
@@ -466,6 +478,15 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
         for (int i = 0; i < 8; ++i) colacc[i] += o[i];
       }
       store8(cw + static_cast<long long>(r) * g.ldc + lc * 8, o);
+    }
+  };
+  if (kBatches > 1) aux_load(ra1, 1);
+  for (int bt = 0; bt < kBatches; bt += 2) {
+    finish(ra0, bt);
+    if (bt + 2 < kBatches) aux_load(ra0, bt + 2);
+    if (bt + 1 < kBatches) {
+      finish(ra1, bt + 1);
+      if (bt + 3 < kBatches) aux_load(ra1, bt + 3);
     }
   }
   if (g.epi == kEpiGeluBwd) {
