@@ -34,6 +34,7 @@ namespace {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2_t __attribute__((ext_vector_type(2)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
@@ -505,6 +506,133 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   gemm_tile<A_KMAJOR, B_KMAJOR, BM, BN>(g, blockIdx.x, blockIdx.y);
 }
 
+// Score-shaped batched products with a short contraction (S = Q K^T, dPd = dC V^T: K = head
+// dimension), lower triangle only.  A tile of such a product is all latency: load two small
+// operand tiles, 32 MFMAs per wavefront, store 32 KB.  Here a workgroup owns one block of
+// 128 rows of one matrix and walks its tiles tn = 0..tm: the A tile stays in LDS, the B tile
+// of the next step is fetched (direct to LDS, two buffers) while the current one is
+// multiplied and stored, and the stores are never waited for, so the kernel runs at the
+// rate its output can be written.  Row blocks are issued longest first.
+template <int KD>
+__global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
+  constexpr int WM = 64, WN = 64, TM = 2, TN = 2;
+  constexpr int kSlabs = KD / kBK;
+  using SL = Slab<128, true>;
+  constexpr int kOpElems = kSlabs * SL::kElems;       // one 128 x KD operand tile
+  constexpr int kOpLoads = kSlabs * SL::kLoadsPerWave;  // direct loads per wavefront per tile
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sB = sA + kOpElems;                           // two buffers
+  bf16_t* sStage = sB + 2 * kOpElems;                   // 4 x (64 x 64)
+
+  const int t = blockIdx.x / g.nz;
+  const int bz = blockIdx.x - t * g.nz;
+  const int tm = g.tiles_m - 1 - t;
+  const int z1 = bz / g.nz2, z2 = bz - z1 * g.nz2;
+  const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2 + static_cast<long long>(tm) * 128 * g.lda;
+  const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
+  bf16_t* Cbase = g.C + z1 * g.c_z1 + z2 * g.c_z2 + static_cast<long long>(tm) * 128 * g.ldc;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+
+  long long offA[SL::kLoadsPerWave], offB[SL::kLoadsPerWave];
+#pragma unroll
+  for (int j = 0; j < SL::kLoadsPerWave; ++j) {
+    offA[j] = SL::global_offset(wave, j, lane, g.lda);
+    offB[j] = SL::global_offset(wave, j, lane, g.ldb);
+  }
+  auto load_tile = [&](const bf16_t* src, const long long (&off)[SL::kLoadsPerWave], bf16_t* dst) {
+#pragma unroll
+    for (int sl = 0; sl < kSlabs; ++sl)
+#pragma unroll
+      for (int j = 0; j < SL::kLoadsPerWave; ++j)
+        __builtin_amdgcn_global_load_lds((global_void_ptr)(src + off[j] + sl * kBK),
+                                         (lds_void_ptr)(dst + sl * SL::kElems + SL::lds_offset(wave, j)), 16, 0, 0);
+  };
+  load_tile(Abase, offA, sA);
+  load_tile(Bbase, offB, sB);
+
+  constexpr int kRowChunks = WN / 8;                    // 8
+  constexpr int kRowsPerStore = kWave / kRowChunks;     // 8
+  constexpr int kStores = WM / kRowsPerStore;           // 8 stores per wavefront per tile
+  bf16_t* stage = sStage + wave * (WM * WN);
+  const int lr = lane / kRowChunks, lc = lane % kRowChunks;
+
+  for (int tn = 0; tn <= tm; ++tn) {
+    // B(tn) (and, the first time, A) has landed: everything older than the previous tile's
+    // stores.  The barrier also says every wavefront has finished reading B(tn - 1).
+    if (tn == 0) wait_vmcnt<0>();
+    else wait_vmcnt<kStores>();
+    block_barrier();
+    if (tn < tm) load_tile(Bbase + static_cast<long long>(tn + 1) * 128 * g.ldb, offB, sB + ((tn + 1) & 1) * kOpElems);
+    const bf16_t* sb = sB + (tn & 1) * kOpElems;
+
+    floatx16_t acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KD / 16; ++kk) {
+      Frag<true> fa[TM], fb[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fa[j] = SL::fragment(sA + (kk >> 1) * SL::kElems, wm0 + 32 * j, kk & 1, lane);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fb[i] = SL::fragment(sb + (kk >> 1) * SL::kElems, wn0 + 32 * i, kk & 1, lane);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i].operand(), fa[j].operand(), acc[i][j], 0, 0, 0);
+    }
+    // round into this wavefront's staging region, then whole rows out, 16 bytes per lane
+    // (acc[i][j][r]: n = wn0 + 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4, m = wm0 + 32 j + lane % 32)
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = 32 * i + 8 * q + 4 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+          const int ml = 32 * j + (lane & 31);
+          uintx2_t o;
+          o[0] = pack_bf16(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1]);
+          o[1] = pack_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          const int chunk = (nl >> 3) ^ (ml & (kRowChunks - 1));
+          // As inline assembly: a store to LDS that the compiler sees is made to wait for
+          // every direct-to-LDS load in flight (here: the next B tile) and, with them, for
+          // the previous tile's stores.  LDS executes a wavefront's accesses in order, so
+          // the row reads below see these writes.
+          typedef __attribute__((address_space(3))) bf16_t* lds_ptr_t;
+          const uint32_t addr = static_cast<uint32_t>(
+              reinterpret_cast<uintptr_t>((lds_ptr_t)(stage + ml * WN + chunk * 8 + (nl & 7))));
+          asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(o) : "memory");
+        }
+      }
+    bf16_t* cw = Cbase + static_cast<long long>(wm0) * g.ldc + tn * 128 + wn0;
+    uintx4_t rows[kStores];
+#pragma unroll
+    for (int u = 0; u < kStores; ++u) {
+      const int r = u * kRowsPerStore + lr;
+      typedef const __attribute__((address_space(3))) bf16_t* lds_cptr_t;
+      const uint32_t addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+          (lds_cptr_t)(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3))));
+      asm volatile("ds_read_b128 %0, %1" : "=v"(rows[u]) : "v"(addr) : "memory");
+    }
+    wait_lgkmcnt0();
+#pragma unroll
+    for (int u = 0; u < kStores; ++u) {
+      asm volatile("" : "+v"(rows[u]));
+      const int r = u * kRowsPerStore + lr;
+      *reinterpret_cast<uintx4_t*>(cw + static_cast<long long>(r) * g.ldc + lc * 8) = rows[u];
+    }
+  }
+}
+
 // An output whose width is an odd multiple of 128: 256 x 256 tiles over the columns that
 // whole tiles cover, and one column of 256 x 128 tiles (`edge`: the same product on the last
 // 128 columns) behind them in the same launch, where they fill the last round of workgroups.
@@ -605,11 +733,33 @@ hipError_t launch_edge(const MfmaGemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int KD>
+hipError_t launch_attn_outer(MfmaGemmArgs a, hipStream_t st) {
+  constexpr size_t smem = (3 * static_cast<size_t>(KD / kBK) * 128 * kBK + 4 * 64 * 64) * sizeof(bf16_t);
+  auto kern = attn_outer_kernel<KD>;
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(smem));
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  a.tiles_m = a.M / 128;
+  a.tiles_n = a.N / 128;
+  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.nz), dim3(kThreads), smem, st, a);
+  return hipGetLastError();
+}
+
 // Tile shape: the largest tile that divides the output, unless a smaller one
 // fills the 256 compute units markedly better (fewer idle units in the last
 // round of workgroups).
 template <bool AK, bool BK_>
 hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
+  if (a.causal == kCausalOutLower && AK && BK_ && a.bias == nullptr && a.epi == kEpiNone) {
+    if (a.K == 128) return launch_attn_outer<128>(a, st);
+    if (a.K == 64) return launch_attn_outer<64>(a, st);
+  }
   if (a.causal != kCausalNone) {
     // attention products: memory-bound.  128 x 128 tiles: the zero padding of the
     // seq x seq operands reaches the next multiple of 128 only, two workgroups fit a
