@@ -83,6 +83,42 @@ def phase_flops(cfg, retain_mask):
     return fwd, rec, bwd
 
 
+def cold_measure(B, torch, cfg, params, x, out, stream, reps=7):
+    """The HBM-bound forward operators timed alone on cold caches: forward under a mask that
+    keeps everything but the operator's output, a 1 GiB read sweep (more than the L2s and the
+    256 MB memory-side cache hold, and it leaves no dirty lines), then lynx_recompute of that
+    one operator between two events.  (The backward kernels have no entry point of their own;
+    their in-situ figures stand alone.)"""
+    full = POLICIES["store_all"]
+    ws_bytes = B.lynx_workspace_bytes(cfg, full)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    layer = B.lynx_layer_create(cfg, (ws.data_ptr() + 255) // 256 * 256, ws_bytes)
+    B.lynx_layer_set_params(layer, params)
+    sweep = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+    work = slot_work(cfg)
+    ops = {"op1_layernorm1": (1 << 1), "op4_softmax_dropout": (1 << 4) | (1 << 5),
+           "op8_bias_dropout_add1": (1 << 8), "op9_layernorm2": (1 << 9), "op11_gelu": (1 << 11)}
+    res = {}
+    for name, seg in ops.items():
+        times = []
+        for k in range(reps):
+            B.lynx_layer_forward(layer, x, out, full & ~seg, k, stream)
+            sweep.sum()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            B.lynx_recompute(layer, seg, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+            B.lynx_layer_reset(layer)
+        ms = sorted(times)[len(times) // 2]
+        gbs = work[name][1] / (ms * 1e-3) / 1e9
+        res[name] = {"ms": round(ms, 4), "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4)}
+        log("cold %-24s %8.4f ms %8.1f GB/s" % (name, ms, gbs))
+    B.lynx_layer_destroy(layer)
+    return res
+
+
 def cpu_baseline(cfg, retain_name):
     """The fp64 oracle as it stands, timed on the host cores on a bounded
     sample: as many micro-batch elements as fit in roughly 20 s (its cost is
@@ -267,6 +303,9 @@ def main():
     ap.add_argument("--standin-workgroups", type=int, default=32)
     ap.add_argument("--slice", action="store_true",
                     help="time the six-layer pipeline-stage slice (C5) instead of one layer")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the HBM-bound forward operators one by one after a 1 GiB read sweep "
+                         "(cold caches) next to their in-situ figures")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (the known-size kernel that "
@@ -411,6 +450,7 @@ def main():
         overlap = overlap_measure(B, torch, layer, x, out, mask, segments, dout, dx, grads, stream,
                                   args.standin_workgroups, max(args.steps, 5))
     B.lynx_layer_destroy(layer)
+    cold = cold_measure(B, torch, cfg, params, x, out, stream) if args.cold else None
 
     work = slot_work(cfg)
     mfma_peak = PEAK_BF16_TFLOPS if cfg.dtype == synth.BF16 else PEAK_FP32_TFLOPS
@@ -466,6 +506,8 @@ def main():
     }
     if overlap is not None:
         result["overlap"] = overlap
+    if cold is not None:
+        result["cold_cache"] = cold
     if heu is not None:
         # recompute_ms here is what phases 1-4 regenerate (hidden behind communication in the
         # paper's schedule); backward_ms includes phase 5, the part left on the critical path

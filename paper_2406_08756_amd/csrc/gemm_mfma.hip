@@ -654,16 +654,17 @@ template <int DBM, int DBN, int WBM, int WBN, int EBM, int EBN>
 __global__ void __launch_bounds__(kThreads)
 gemm_mfma_pair_kernel(MfmaGemmArgs wgrad, MfmaGemmArgs wedge, MfmaGemmArgs dgrad, int n_w, int n_e) {
   const int x = static_cast<int>(blockIdx.x);
+  // the input gradient starts at a multiple of 8 workgroups, so that its tile order, which
+  // takes workgroup id mod 8 for the XCD, still holds; the few workgroups in between idle
+  const int n_pad = (n_w + n_e + 7) & ~7;
   if (x < n_w) {
     if (wgrad.k_splits > 1) gemm_tile<false, false, WBM, WBN, true>(wgrad, x, 0);
     else gemm_tile<false, false, WBM, WBN>(wgrad, x, 0);
   } else if (EBM != 0 && x < n_w + n_e) {
-    if constexpr (EBM != 0) {
-      if (wedge.k_splits > 1) gemm_tile<false, false, EBM, EBN, true>(wedge, x - n_w, 0);
-      else gemm_tile<false, false, EBM, EBN>(wedge, x - n_w, 0);
-    }
-  } else
-    gemm_tile<true, false, DBM, DBN>(dgrad, x - n_w - n_e, 0);
+    if constexpr (EBM != 0) gemm_tile<false, false, EBM, EBN>(wedge, x - n_w, 0);
+  } else if (x >= n_pad) {
+    gemm_tile<true, false, DBM, DBN>(dgrad, x - n_pad, 0);
+  }
 }
 
 // C[m][n] = round(sum over the K ranges, in range order, of partial[split][m][n]).
@@ -832,7 +833,9 @@ PairPlan plan_pair(int wM, int wN, int wK, int dM, int dN, int dK) {
   }
   const double work_d = static_cast<double>(dM / p.dbm) * (dN / p.dbn) * slabs_d * cost(p.dbm, p.dbn);
   const double ideal = (work_w + work_d) / 256.0;
-  const bool cut = wK % (2 * kBK) == 0 && wK >= 2048 && longest > kPairCutFraction * ideal;
+  // (a weight gradient with an edge strip is never cut: with half a round of whole tiles or
+  // more its tiles are not the ones the launch waits for)
+  const bool cut = p.edge == 0 && wK % (2 * kBK) == 0 && wK >= 2048 && longest > kPairCutFraction * ideal;
   p.k_splits = cut ? 2 : 1;
   return p;
 }
@@ -867,23 +870,18 @@ hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, const PairPlan& plan, hip
       e.N = 128;
       w.N = body_cols;
     }
-    if (w.k_splits > 1) e.partial = w.partial + static_cast<long long>(w.k_splits) * w.M * w.N;
     e.tiles_m = e.M / EBM; e.tiles_n = e.N / EBN;
-    n_e = e.tiles_m * e.tiles_n * e.k_splits;
+    n_e = e.tiles_m * e.tiles_n;
   }
   w.tiles_m = w.M / WBM; w.tiles_n = w.N / WBN;
   d.tiles_m = d.M / DBM; d.tiles_n = d.N / DBN;
   const int n_w = w.tiles_m * w.tiles_n * w.k_splits;
-  hipLaunchKernelGGL(kern, dim3(n_w + n_e + d.tiles_m * d.tiles_n), dim3(kThreads), smem, st, w, e, d, n_w, n_e);
+  const int n_pad = (n_w + n_e + 7) & ~7;
+  hipLaunchKernelGGL(kern, dim3(n_pad + d.tiles_m * d.tiles_n), dim3(kThreads), smem, st, w, e, d, n_w, n_e);
   if (w.k_splits > 1) {
     const long long vecs = static_cast<long long>(w.M) * (w.N / 8);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>((vecs + 255) / 256)), dim3(256), 0, st,
                        w.partial, w.C, w.M, w.N, w.ldc, w.k_splits);
-    if (EBM != 0) {
-      const long long evecs = static_cast<long long>(e.M) * (e.N / 8);
-      hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>((evecs + 255) / 256)), dim3(256), 0, st,
-                         e.partial, e.C, e.M, e.N, e.ldc, e.k_splits);
-    }
   }
   return hipGetLastError();
 }
