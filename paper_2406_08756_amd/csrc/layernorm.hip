@@ -12,6 +12,7 @@ namespace {
 
 constexpr int kBwdThreads = 256;
 constexpr int kBwdMaxBlocks = 512;
+constexpr int kFwdStreamBlocks = 1024;
 
 // Sum over the BS threads of a workgroup, every thread gets the total; `slot` is this
 // call's own LDS row, so two calls need no barrier between them.  Fixed combination order.
@@ -81,6 +82,87 @@ layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
   if (threadIdx.x == 0) {
     mean[r] = mu;
     rstd[r] = rs;
+  }
+}
+
+// The same operator for many rows: a resident set of workgroups, each walking rows of its
+// XCD's eighth of the tensor, with the next row's vectors requested before the current
+// row is reduced and stored, so a workgroup always has a row in flight (a second row ahead
+// and other workgroup counts from 512 to 4096 measure the same or worse).
+template <typename T, int BS, int NC>
+__global__ void __launch_bounds__(BS)
+layernorm_fwd_stream_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                            const T* __restrict__ beta, T* __restrict__ y, float* __restrict__ mean,
+                            float* __restrict__ rstd, int rows, int cols, float eps) {
+  __shared__ float red[2][BS / kWave];
+  const int per_xcd = rows >> 3, groups = gridDim.x >> 3;  // rows % 8 == 0, gridDim.x % 8 == 0
+  const int first = blockIdx.x >> 3, xcd_row0 = (blockIdx.x & 7) * per_xcd;
+  const float inv_n = 1.0f / static_cast<float>(cols);
+  bool on[NC];
+  int j0[NC];
+  Raw8<T> graw[NC], braw[NC], cur[NC], nxt[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    j0[c] = (threadIdx.x + c * BS) * 8;
+    on[c] = j0[c] < cols;
+    if (!on[c]) j0[c] = 0;  // counts for nothing, stores nothing
+    load_raw(gamma + j0[c], graw[c]);
+    load_raw(beta + j0[c], braw[c]);
+  }
+  if (first < per_xcd) {
+    const size_t base = static_cast<size_t>(xcd_row0 + first) * cols;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) load_raw(x + base + j0[c], cur[c]);
+  }
+  for (int i = first; i < per_xcd; i += groups) {
+    const int r = xcd_row0 + i;
+    const bool more = i + groups < per_xcd;
+    if (more) {
+      const size_t nbase = static_cast<size_t>(r + groups) * cols;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) load_raw(x + nbase + j0[c], nxt[c]);
+    }
+    float v[NC][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      unpack(cur[c], v[c]);
+      const float w = on[c] ? 1.0f : 0.0f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) sum += w * v[c][k];
+    }
+    const float mu = block_sum<BS>(sum, red[0]) * inv_n;
+    float sq = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const float w = on[c] ? 1.0f : 0.0f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        v[c][k] -= mu;
+        sq += w * (v[c][k] * v[c][k]);
+      }
+    }
+    const float rs = rsqrtf(block_sum<BS>(sq, red[1]) * inv_n + eps);
+    const size_t base = static_cast<size_t>(r) * cols;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      if (on[c]) {
+        float g[8], b[8];
+        unpack(graw[c], g);
+        unpack(braw[c], b);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[c][k] = g[k] * (v[c][k] * rs) + b[k];
+        store8(y + base + j0[c], v[c]);
+      }
+    }
+    if (threadIdx.x == 0) {
+      mean[r] = mu;
+      rstd[r] = rs;
+    }
+    if (more) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) cur[c] = nxt[c];
+    }
   }
 }
 
@@ -255,6 +337,25 @@ hipError_t layernorm_fwd(int dtype, const void* x, const void* gamma, const void
                        static_cast<const float*>(x), static_cast<const float*>(gamma),             \
                        static_cast<const float*>(beta), static_cast<float*>(y), mean, rstd, rows,  \
                        cols, eps)
+  // many rows: the streaming form, 1024 resident workgroups (must give the same bits as the
+  // one-row form: same per-thread columns, same reduction order)
+  if (rows % 8 == 0 && rows >= 4 * kFwdStreamBlocks && vecs > 512) {
+#define CALLS(BS, NC)                                                                              \
+  if (dtype == 1)                                                                                  \
+    hipLaunchKernelGGL((layernorm_fwd_stream_kernel<bf16_t, BS, NC>), dim3(kFwdStreamBlocks),      \
+                       dim3(BS), 0, st, static_cast<const bf16_t*>(x),                             \
+                       static_cast<const bf16_t*>(gamma), static_cast<const bf16_t*>(beta),        \
+                       static_cast<bf16_t*>(y), mean, rstd, rows, cols, eps);                      \
+  else                                                                                             \
+    hipLaunchKernelGGL((layernorm_fwd_stream_kernel<float, BS, NC>), dim3(kFwdStreamBlocks),       \
+                       dim3(BS), 0, st, static_cast<const float*>(x),                              \
+                       static_cast<const float*>(gamma), static_cast<const float*>(beta),          \
+                       static_cast<float*>(y), mean, rstd, rows, cols, eps)
+    if (vecs <= 768) { CALLS(256, 3); }
+    else { CALLS(256, 4); }
+#undef CALLS
+    return hipGetLastError();
+  }
   // up to four vectors per thread
   if (vecs <= 64) { CALL(64, 1); }
   else if (vecs <= 128) { CALL(64, 2); }

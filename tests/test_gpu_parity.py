@@ -45,6 +45,10 @@ SMALL = {
     # 128-wide input-gradient tiles and the GeLU backward in their epilogue
     "pair128_bf16": synth.LayerConfig(synth.BF16, 256, 2, 128, 384, 256, 2, tp_size=1,
                                       dropout_p=0.1, seed=13, layer_id=8),
+    # thousands of rows wider than 4096: the streaming LayerNorm forward (ragged last vector
+    # group per thread); everything else tiny
+    "ln_stream_bf16": synth.LayerConfig(synth.BF16, 4104, 1, 8, 8, 128, 32, tp_size=1,
+                                        dropout_p=0.1, seed=14, layer_id=10),
     "C1": synth.CONFIGS["C1"],
     "nodrop_bf16": synth.LayerConfig(synth.BF16, 256, 2, 64, 512, 128, 1, dropout_p=0.0),
     "minimal_f32": synth.LayerConfig(synth.F32, 8, 1, 8, 8, 8, 1, dropout_p=0.5, seed=9),
@@ -112,7 +116,7 @@ def test_store_all_forward_and_backward_match_oracle(name):
 
 
 @pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16", "tiles128_bf16", "tiles256_bf16", "long_seq_bf16",
-                                  "wide_bf16", "edge_bf16", "pair128_bf16"])
+                                  "wide_bf16", "edge_bf16", "pair128_bf16", "ln_stream_bf16"])
 def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
     cfg = SMALL[name]
     params = synth.make_params(cfg, random_ln=True)
