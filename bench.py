@@ -482,6 +482,12 @@ def main():
                 "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": traffic,
                 "traffic_unit": "bytes per launch (counter runs under profiles/, not live)",
                 "ms_per_launch": kernels[dom]["ms"]}
+    fused = {"b12_fc2_dgrad_wgrad": "the launch also applies the GeLU backward and sums the FC1 bias gradient in its "
+                                    "store pass (reads U, T*f*e bytes more); achieved counts the matrix flops only",
+             "op7_attn_proj_gemm": "the launch also applies bias + dropout + residual in its store pass",
+             "op12_fc2_gemm": "the launch also applies bias + dropout + residual in its store pass"}
+    if dom.split("/")[-1] in fused and cfg.dtype == synth.BF16:
+        roofline["note"] = fused[dom.split("/")[-1]]
 
     fwd_f, rec_f, bwd_f = phase_flops(cfg, mask)
     rb_ms = rec_ms + bwd_ms
