@@ -65,6 +65,8 @@ def slot_work(cfg):
         "b3_dq": ("mfma", att), "b3_dk": ("mfma", att), "b2_qkv_dgrad_wgrad": ("mfma", 2 * lin(3 * p, h)),
         "b2_bias_grad": ("hbm", T * 3 * p * e),
         "b1_layernorm1_bwd": ("hbm", 4 * T * h * e),
+        # dPd = dC V^T with the dropout + softmax backward in its store pass: reads P, writes dS
+        "b6_rowdot": ("hbm", 2 * T * p * e), "b654_dscores": ("hbm", 2 * tri * e),
     }
 
 

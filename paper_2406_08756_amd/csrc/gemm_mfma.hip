@@ -69,6 +69,10 @@ struct MfmaGemmArgs {
   bf16_t* plain;
   float* colsum_partial;
   DropoutKey key;
+  // kEpiSoftmaxBwd (attention): per-row dot products, 1 / sqrt(d), dropout index map
+  const float* rowdot;
+  float scale;
+  int global_heads, head0;
 };
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -633,6 +637,187 @@ __global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
   }
 }
 
+// dS from dC, V and P in one launch: the score-shaped product dPd = dC V^T with the backward
+// of dropout and softmax (B5 + B4) in its store pass, so dPd is never written:
+//   dS = scale P (keep c round(dPd) - dot),  dot_i = sum_j dP_ij P_ij.
+// The row dot product comes in from a small kernel that forms it as sum_dd dC[i, dd] C[i, dd]
+// (= sum_j dPd_ij Pd_ij since Pd V = C: the same number up to the rounding of Pd and dPd), so
+// one pass over the tiles suffices.  Same walk as attn_outer_kernel (a workgroup owns a block
+// of 128 rows, the A tile stays in LDS), but the store pass is long here (a Philox call per
+// 8 elements), so: one B buffer, which doubles as the staging area; the next B tile and the
+// next tile's vectors of P are requested just before the store pass and arrive during it;
+// and the 64 KB of LDS let two workgroups share a compute unit.  The loads of P are inline
+// assembly with waits counted by hand: loads the compiler tracks would be waited for at
+// the loop's back edge together with everything issued after them.
+template <int KD>
+__global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs g) {
+  constexpr int WM = 64, WN = 64, TM = 2, TN = 2;
+  constexpr int kSlabs = KD / kBK;
+  using SL = Slab<128, true>;
+  constexpr int kOpElems = kSlabs * SL::kElems;  // one 128 x KD operand tile
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sB = sA + kOpElems;
+  static_assert(kOpElems >= 4 * WM * WN || KD < 128, "staging fits the B buffer");
+
+  const int t = blockIdx.x / g.nz;
+  const int bz = blockIdx.x - t * g.nz;
+  const int tm = g.tiles_m - 1 - t;
+  const int z1 = bz / g.nz2, z2 = bz - z1 * g.nz2;
+  const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2 + static_cast<long long>(tm) * 128 * g.lda;
+  const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
+  bf16_t* Cbase = g.C + z1 * g.c_z1 + z2 * g.c_z2 + static_cast<long long>(tm) * 128 * g.ldc;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+
+  long long offA[SL::kLoadsPerWave], offB[SL::kLoadsPerWave];
+#pragma unroll
+  for (int j = 0; j < SL::kLoadsPerWave; ++j) {
+    offA[j] = SL::global_offset(wave, j, lane, g.lda);
+    offB[j] = SL::global_offset(wave, j, lane, g.ldb);
+  }
+  auto load_tile = [&](const bf16_t* src, const long long (&off)[SL::kLoadsPerWave], bf16_t* dst) {
+#pragma unroll
+    for (int sl = 0; sl < kSlabs; ++sl)
+#pragma unroll
+      for (int j = 0; j < SL::kLoadsPerWave; ++j)
+        __builtin_amdgcn_global_load_lds((global_void_ptr)(src + off[j] + sl * kBK),
+                                         (lds_void_ptr)(dst + sl * SL::kElems + SL::lds_offset(wave, j)), 16, 0, 0);
+  };
+  constexpr int kTileLoads = kSlabs * SL::kLoadsPerWave;  // direct loads per wavefront per tile
+  load_tile(Abase, offA, sA);
+  load_tile(Bbase, offB, sB);
+
+  constexpr int kRowChunks = WN / 8;                 // 8
+  constexpr int kRowsPerStore = kWave / kRowChunks;  // 8
+  constexpr int kStores = WM / kRowsPerStore;        // 8 rows of P / stores per lane per tile
+  bf16_t* stage = sB + wave * (WM * WN);
+  const int lr = lane / kRowChunks, lc = lane % kRowChunks;
+
+  // this lane's eight rows: dot products, dropout indices, vectors of P (two sets)
+  const bf16_t* Pw = g.aux + z1 * g.c_z1 + z2 * g.c_z2 + static_cast<long long>(tm * 128 + wm0) * g.ldc + wn0 + lc * 8;
+  const uint64_t rows_before = (static_cast<uint64_t>(z1) * g.global_heads + g.head0 + z2) * g.M;
+  float dot[kStores];
+  uint64_t gidx[kStores];
+  uintx4_t p0[kStores], p1[kStores];
+  auto request_p = [&](int tn, uintx4_t (&pv)[kStores]) {
+#pragma unroll
+    for (int u = 0; u < kStores; ++u) {
+      const bf16_t* src = Pw + static_cast<long long>(u * kRowsPerStore + lr) * g.ldc + tn * 128;
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(pv[u]) : "v"(src) : "memory");
+    }
+  };
+  request_p(0, p0);
+#pragma unroll
+  for (int u = 0; u < kStores; ++u) {
+    const int i = tm * 128 + wm0 + u * kRowsPerStore + lr;
+    dot[u] = g.rowdot[static_cast<long long>(bz) * g.M + i];
+    gidx[u] = (rows_before + i) * static_cast<uint64_t>(g.N) + wn0 + lc * 8;
+  }
+  // (a use: the compiler waits for these loads here, once, and tracks nothing into the loop)
+#pragma unroll
+  for (int u = 0; u < kStores; ++u) asm volatile("" : "+v"(dot[u]));
+
+  // One tile; `pc` holds this tile's vectors of P, `pn` receives the next tile's.
+  auto tile_step = [&](const int tn, uintx4_t (&pc)[kStores], uintx4_t (&pn)[kStores]) {
+    // B(tn) has landed.  Issued after it: the previous step's requests for P and its stores
+    // (nothing the first time, when everything issued so far is waited for).
+    if (tn == 0) wait_vmcnt<0>();
+    else wait_vmcnt<2 * kStores>();
+    block_barrier();
+    floatx16_t acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KD / 16; ++kk) {
+      Frag<true> fa[TM], fb[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fa[j] = SL::fragment(sA + (kk >> 1) * SL::kElems, wm0 + 32 * j, kk & 1, lane);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fb[i] = SL::fragment(sB + (kk >> 1) * SL::kElems, wn0 + 32 * i, kk & 1, lane);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i].operand(), fa[j].operand(), acc[i][j], 0, 0, 0);
+    }
+    block_barrier();  // every wavefront has read B(tn): its buffer becomes the staging area
+    // round into this wavefront's quarter, read whole rows back, 16 bytes per lane
+    // (acc[i][j][r]: n = wn0 + 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4, m = wm0 + 32 j + lane % 32)
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = 32 * i + 8 * q + 4 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+          const int ml = 32 * j + (lane & 31);
+          uintx2_t o;
+          o[0] = pack_bf16(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1]);
+          o[1] = pack_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          const int chunk = (nl >> 3) ^ (ml & (kRowChunks - 1));
+          typedef __attribute__((address_space(3))) bf16_t* lds_ptr_t;
+          const uint32_t addr = static_cast<uint32_t>(
+              reinterpret_cast<uintptr_t>((lds_ptr_t)(stage + ml * WN + chunk * 8 + (nl & 7))));
+          asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(o) : "memory");
+        }
+      }
+    uintx4_t rows[kStores];
+#pragma unroll
+    for (int u = 0; u < kStores; ++u) {
+      const int r = u * kRowsPerStore + lr;
+      typedef const __attribute__((address_space(3))) bf16_t* lds_cptr_t;
+      const uint32_t addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+          (lds_cptr_t)(stage + r * WN + ((lc ^ (r & (kRowChunks - 1))) << 3))));
+      asm volatile("ds_read_b128 %0, %1" : "=v"(rows[u]) : "v"(addr) : "memory");
+    }
+    wait_lgkmcnt0();
+#pragma unroll
+    for (int u = 0; u < kStores; ++u) asm volatile("" : "+v"(rows[u]));
+    block_barrier();  // every wavefront has its rows: the buffer can take the next B tile
+    if (tn < tm) {
+      load_tile(Bbase + static_cast<long long>(tn + 1) * 128 * g.ldb, offB, sB);
+      request_p(tn + 1, pn);
+    }
+    // this tile's P: requested a step ago; issued since: the previous step's stores and, if
+    // there is a next tile, its B tile and its P
+    if (tn == 0) {
+      // (waited for at the top)
+    } else if (tn < tm) {
+      wait_vmcnt<2 * kStores + kTileLoads>();
+    } else {
+      wait_vmcnt<kStores>();
+    }
+    bf16_t* cw = Cbase + static_cast<long long>(wm0) * g.ldc + tn * 128 + wn0;
+#pragma unroll
+    for (int u = 0; u < kStores; ++u) {
+      asm volatile("" : "+v"(pc[u]));
+      const int r = u * kRowsPerStore + lr;
+      Raw8<bf16_t> dv, pv;
+      dv.v = make_uint4(rows[u][0], rows[u][1], rows[u][2], rows[u][3]);
+      pv.v = make_uint4(pc[u][0], pc[u][1], pc[u][2], pc[u][3]);
+      float dp[8], pr[8], ds[8];
+      unpack(dv, dp);
+      unpack(pv, pr);
+      dropout_apply8(g.key, (gidx[u] + tn * 128) >> 3, dp);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ds[k] = g.scale * (pr[k] * (dp[k] - dot[u]));
+      store8(cw + static_cast<long long>(r) * g.ldc + lc * 8, ds);
+    }
+  };
+  // two tiles per trip, so the two sets of P registers swap roles without being copied
+  for (int tn = 0; tn <= tm; tn += 2) {
+    tile_step(tn, p0, p1);
+    if (tn + 1 <= tm) tile_step(tn + 1, p1, p0);
+  }
+}
+
 // An output whose width is an odd multiple of 128: 256 x 256 tiles over the columns that
 // whole tiles cover, and one column of 256 x 128 tiles (`edge`: the same product on the last
 // 128 columns) behind them in the same launch, where they fill the last round of workgroups.
@@ -752,6 +937,24 @@ hipError_t launch_attn_outer(MfmaGemmArgs a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int KD>
+hipError_t launch_attn_dscores(MfmaGemmArgs a, hipStream_t st) {
+  constexpr size_t smem = 2 * static_cast<size_t>(KD / kBK) * 128 * kBK * sizeof(bf16_t);
+  auto kern = attn_dscores_kernel<KD>;
+  static bool configured = false;
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(smem));
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  a.tiles_m = a.M / 128;
+  a.tiles_n = a.N / 128;
+  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.nz), dim3(kThreads), smem, st, a);
+  return hipGetLastError();
+}
+
 // Tile shape: the largest tile that divides the output, unless a smaller one
 // fills the 256 compute units markedly better (fewer idle units in the last
 // round of workgroups).
@@ -761,6 +964,7 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
     if (a.K == 128) return launch_attn_outer<128>(a, st);
     if (a.K == 64) return launch_attn_outer<64>(a, st);
   }
+  if (a.epi == kEpiSoftmaxBwd) return launch_attn_dscores<128>(a, st);  // gemm_mfma_supported: K = 128
   if (a.causal != kCausalNone) {
     // attention products: memory-bound.  128 x 128 tiles: the zero padding of the
     // seq x seq operands reaches the next multiple of 128 only, two workgroups fit a
@@ -906,6 +1110,11 @@ MfmaGemmArgs make_args(const GemmDesc& d) {
     a.plain = static_cast<bf16_t*>(d.epi.plain);
     a.colsum_partial = d.epi.colsum_partial;
     if (d.epi.kind == kEpiBiasDropoutAdd) a.key = make_dropout_key(d.epi.dp, d.epi.site);
+    if (d.epi.kind == kEpiSoftmaxBwd) {
+      a.key = make_dropout_key(d.epi.dp, 0);
+      a.rowdot = d.epi.rowdot; a.scale = d.epi.scale;
+      a.global_heads = d.epi.global_heads; a.head0 = d.epi.head0;
+    }
   }
   return a;
 }
@@ -926,6 +1135,14 @@ bool gemm_mfma_supported(int dtype, const GemmDesc& d) {
   if (reinterpret_cast<uintptr_t>(d.C) & 15) return false;
   if (d.bias != nullptr && (reinterpret_cast<uintptr_t>(d.bias) & 7)) return false;
   if (d.epi.kind != kEpiNone) {
+    if (d.epi.kind == kEpiSoftmaxBwd) {
+      // only the row-block kernel of the score-shaped products carries it (head dimension 128:
+      // the staging area is the B buffer)
+      if (d.causal != kCausalOutLower || d.bias != nullptr || d.K != 128) return false;
+      if (!(d.a_sk == 1 && d.b_sk == 1)) return false;
+      if (d.epi.aux == nullptr || (reinterpret_cast<uintptr_t>(d.epi.aux) & 15) || d.epi.rowdot == nullptr) return false;
+      return true;
+    }
     if (d.epi.kind != kEpiBiasDropoutAdd && d.epi.kind != kEpiGeluBwd) return false;
     if (d.causal != kCausalNone || d.nz1 * d.nz2 != 1 || d.bias != nullptr) return false;
     if (d.epi.aux == nullptr || (reinterpret_cast<uintptr_t>(d.epi.aux) & 15) || d.epi.aux_ld % 8) return false;
@@ -961,7 +1178,7 @@ bool gemm_mfma_pair_supported(int dtype, const GemmDesc& dgrad, const GemmDesc& 
   if (dgrad.causal != kCausalNone || wgrad.causal != kCausalNone) return false;
   if (!(dgrad.a_sk == 1 && dgrad.b_sn == 1 && dgrad.b_sk != 1)) return false;  // A K-major, B MN-major
   if (!(wgrad.a_sm == 1 && wgrad.a_sk != 1 && wgrad.b_sn == 1 && wgrad.b_sk != 1)) return false;
-  if (wgrad.epi.kind != kEpiNone || dgrad.epi.kind == kEpiBiasDropoutAdd) return false;
+  if (wgrad.epi.kind != kEpiNone || (dgrad.epi.kind != kEpiNone && dgrad.epi.kind != kEpiGeluBwd)) return false;
   const PairPlan p = plan_pair(wgrad.M, wgrad.N, wgrad.K, dgrad.M, dgrad.N, dgrad.K);
   if (p.dbm != 256) return false;
   if (p.wbm == 128 && p.wbn == 128) return false;

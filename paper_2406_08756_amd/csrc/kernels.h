@@ -68,6 +68,11 @@ hipError_t dropout_bwd(int dtype, const void* dout, void* din, void* dbias, floa
 // dbias[c] = sum_r x[r, c]
 hipError_t column_sum(int dtype, const void* x, void* dbias, float* scratch, int rows, int cols,
                       hipStream_t st);
+// out[(bi * a + hd) * s + i] = sum_dd x[t, hd * d + dd] * y[t, hd * d + dd], t = bi * s + i (fp32);
+// x and y are [T, a * d] with row stride ld.  With x = dC and y = C this is the row dot
+// product sum_j dP_ij P_ij of the softmax backward.
+hipError_t attn_rowdot(int dtype, const void* x, const void* y, float* out, int b, int a, int s, int d,
+                       long long ld, hipStream_t st);
 // keep-mask bytes for parity checks: n elements starting at flat index 0 of
 // site 1/2, or the [b, a, s, s] tensor of site 0.
 hipError_t dropout_mask_hidden(uint8_t* out, size_t n, int site, DropoutParams dp, hipStream_t st);
@@ -93,7 +98,12 @@ enum GemmEpilogueKind : int {
   // GeLU backward (input gradient of FC2 only, inside gemm_pair): C = P gelu'(aux) and
   // colsum_out[n] = sum_m C[m, n] (the FC1 bias gradient), reduced in two fixed-order stages
   // through `colsum_partial` (gemm_colsum_partial_bytes).
-  kEpiGeluBwd = 2
+  kEpiGeluBwd = 2,
+  // dropout + softmax backward (B5 + B4) on the score-shaped product dPd = dC V^T (causal,
+  // batched): C = dS = scale aux (keep c P - rowdot), aux = the softmax output P in the layout
+  // of C, rowdot[z * M + i] the row's sum_j dP_ij P_ij (attn_rowdot), dropout site 0 with the
+  // attention index map (global_heads, head0).  dPd itself is never stored.
+  kEpiSoftmaxBwd = 4
 };
 struct GemmEpilogue {
   int kind;
@@ -105,6 +115,9 @@ struct GemmEpilogue {
   DropoutParams dp;       // (1)
   float* colsum_partial;  // (2)
   void* colsum_out;       // (2) [N], storage dtype
+  const float* rowdot;    // (4)
+  float scale;            // (4)
+  int global_heads, head0;  // (4)
 };
 
 // C[z][m, n] = sum_k A[z][m, k] * B[z][k, n] (+ bias[n]), z = (z1, z2) a

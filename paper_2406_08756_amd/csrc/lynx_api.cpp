@@ -142,7 +142,7 @@ struct Ctx {  // one pass (rehearsal or real) of a call
 // profile slots: 1..13 = forward operators; then the backward kernels in order
 enum BackwardSlot {
   kB13Dropout = 14, kB12Grads, kB11Gelu, kB10Grads, kB98LayerNormDropout, kB7Grads, kB6DPd,
-  kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kNumSlots
+  kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kB6RowDot, kB654DScores, kNumSlots
 };
 static_assert(kNumSlots <= LYNX_PROFILE_SLOTS, "profile slots");
 const char* const kSlotNames[kNumSlots] = {
@@ -151,7 +151,7 @@ const char* const kSlotNames[kNumSlots] = {
     "op11_gelu", "op12_fc2_gemm", "op13_bias_dropout_add2", "b13_dropout_bwd",
     "b12_fc2_dgrad_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad_wgrad",
     "b98_layernorm2_dropout_bwd", "b7_proj_dgrad_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd", "b3_dq",
-    "b3_dk", "b2_qkv_dgrad_wgrad", "b2_bias_grad", "b1_layernorm1_bwd"};
+    "b3_dk", "b2_qkv_dgrad_wgrad", "b2_bias_grad", "b1_layernorm1_bwd", "b6_rowdot", "b654_dscores"};
 
 char* act_ptr(const Ctx& cx, int i) {
   if (i == 0) return const_cast<char*>(static_cast<const char*>(cx.L->x));
@@ -578,24 +578,49 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_LAUNCH(cx, kB7Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T, D.h, D.p),
                                                   linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h, D.p), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_do);
-  free_act(cx, 6);
-  // B6: C = Pd V
+  // B6: C = Pd V (C itself is read once more below, for the row dot products)
   LYNX_TRY(alloc_temp(cx, D.ss * e, &t_dpd));
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * 3 * D.p * e, &t_dqkv));
   char* dqkv = temp_ptr(cx, t_dqkv);
   const char* qkv = act_ptr(cx, 2);
-  LYNX_LAUNCH(cx, kB6DPd, lynx::gemm(dt, attn_outer(temp_ptr(cx, t_dc), D.p, col_block(qkv, D, 2), 3 * D.p,
-                                            temp_ptr(cx, t_dpd), D), cx.st));
+  // dPd = dC V^T, then B5 + B4: Pd = keep0 P c, P = softmax(S / sqrt(d)).  Where the row-block
+  // kernel applies, the store pass of the product forms dS directly (dPd is never written);
+  // the row dot products sum_j dP_ij P_ij it needs equal sum_dd dC[i, dd] C[i, dd] and come
+  // from a small kernel over dC and C.  Otherwise dPd is stored and dS overwrites it.
+  GemmDesc dpd = attn_outer(temp_ptr(cx, t_dc), D.p, col_block(qkv, D, 2), 3 * D.p, temp_ptr(cx, t_dpd), D);
+  Temp t_rowdot;
+  LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.b) * D.a * D.s * sizeof(float), &t_rowdot));
+  dpd.epi.kind = lynx::kEpiSoftmaxBwd;
+  dpd.epi.aux = act_ptr(cx, 4);
+  dpd.epi.aux_ld = D.s;
+  dpd.epi.rowdot = reinterpret_cast<const float*>(temp_ptr(cx, t_rowdot));
+  dpd.epi.scale = 1.0f / sqrtf(static_cast<float>(D.d));
+  dpd.epi.dp = dropout_params(L);
+  dpd.epi.global_heads = D.a * L->cfg.tp_size;
+  dpd.epi.head0 = L->cfg.tp_rank * D.a;
+  const bool fused_ds = lynx::gemm_mfma_supported(dt, dpd);
+  if (fused_ds) {
+    LYNX_LAUNCH(cx, kB6RowDot, lynx::attn_rowdot(dt, temp_ptr(cx, t_dc), act_ptr(cx, 6),
+                                                 reinterpret_cast<float*>(temp_ptr(cx, t_rowdot)), D.b, D.a, D.s,
+                                                 D.d, D.p, cx.st));
+    LYNX_LAUNCH(cx, kB654DScores, lynx::gemm_mfma(dpd, cx.st));
+  } else {
+    dpd.epi = lynx::GemmEpilogue{};
+    LYNX_LAUNCH(cx, kB6DPd, lynx::gemm(dt, dpd, cx.st));
+  }
+  free_temp(cx, &t_rowdot);
   LYNX_LAUNCH(cx, kB6DV, lynx::gemm(dt, attn_cols(act_ptr(cx, 5), temp_ptr(cx, t_dc), D.p,
                                            const_cast<char*>(col_block(dqkv, D, 2)), 3 * D.p, D),
                              cx.st));
   free_temp(cx, &t_dc);
   free_act(cx, 5);
-  // B5 + B4: Pd = keep0 P c, P = softmax(S / sqrt(d)); dS overwrites dPd
-  LYNX_LAUNCH(cx, kB54Softmax, lynx::softmax_dropout_bwd(dt, temp_ptr(cx, t_dpd), act_ptr(cx, 4),
-                                            temp_ptr(cx, t_dpd), attn_shape(L),
-                                            1.0f / sqrtf(static_cast<float>(D.d)), dropout_params(L),
-                                            cx.st));
+  free_act(cx, 6);
+  if (!fused_ds) {
+    LYNX_LAUNCH(cx, kB54Softmax, lynx::softmax_dropout_bwd(dt, temp_ptr(cx, t_dpd), act_ptr(cx, 4),
+                                              temp_ptr(cx, t_dpd), attn_shape(L),
+                                              1.0f / sqrtf(static_cast<float>(D.d)), dropout_params(L),
+                                              cx.st));
+  }
   free_act(cx, 4);
   // B3: S = Q K^T
   LYNX_LAUNCH(cx, kB3DQ, lynx::gemm(dt, attn_rows(temp_ptr(cx, t_dpd), col_block(qkv, D, 1), 3 * D.p,

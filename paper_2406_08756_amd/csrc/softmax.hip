@@ -148,6 +148,36 @@ softmax_dropout_bwd_kernel(const T* dPd, const T* __restrict__ P, T* dS,  // dS 
   }
 }
 
+// Row dot products over the head dimension: 16 lanes per (token, head) pair.
+template <typename T>
+__global__ void __launch_bounds__(256)
+attn_rowdot_kernel(const T* __restrict__ x, const T* __restrict__ y, float* __restrict__ out, int a, int s,
+                   int d, long long ld, long long pairs) {
+  const long long q = static_cast<long long>(blockIdx.x) * 16 + (threadIdx.x >> 4);
+  const int l = threadIdx.x & 15;
+  float acc = 0.f;
+  long long t = 0;
+  int hd = 0;
+  if (q < pairs) {
+    t = q / a;
+    hd = static_cast<int>(q - t * a);
+    const size_t base = static_cast<size_t>(t) * ld + static_cast<size_t>(hd) * d;
+    for (int v = l; v * 8 < d; v += 16) {
+      float xv[8], yv[8];
+      load8(x + base + v * 8, xv);
+      load8(y + base + v * 8, yv);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc += xv[k] * yv[k];
+    }
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 16);
+  if (q < pairs && l == 0) {
+    const long long bi = t / s, i = t - bi * s;
+    out[(bi * a + hd) * s + i] = acc;
+  }
+}
+
 // registers hold ceil(s / 512) vectors per lane
 #define LYNX_DISPATCH_NC(s, CALL)            \
   if ((s) <= 512) { CALL(1); }               \
@@ -192,6 +222,20 @@ hipError_t attn_dropout_fwd(int dtype, const void* P, void* Pd, AttnShape sh, Dr
     hipLaunchKernelGGL((attn_dropout_fwd_kernel<float>), grid, block, 0, st,
                        static_cast<const float*>(P), static_cast<float*>(Pd), sh.s, sh.a,
                        sh.global_heads, sh.head0, key);
+  return hipGetLastError();
+}
+
+hipError_t attn_rowdot(int dtype, const void* x, const void* y, float* out, int b, int a, int s, int d,
+                       long long ld, hipStream_t st) {
+  if (d % 8 || ld % 8) return hipErrorInvalidValue;
+  const long long pairs = static_cast<long long>(b) * s * a;
+  const dim3 grid(static_cast<unsigned>((pairs + 15) / 16));
+  if (dtype == 1)
+    hipLaunchKernelGGL((attn_rowdot_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(y), out, a, s, d, ld, pairs);
+  else
+    hipLaunchKernelGGL((attn_rowdot_kernel<float>), grid, dim3(256), 0, st, static_cast<const float*>(x),
+                       static_cast<const float*>(y), out, a, s, d, ld, pairs);
   return hipGetLastError();
 }
 
