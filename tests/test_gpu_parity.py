@@ -25,7 +25,7 @@ SMALL = {
     "tiles_bf16": synth.LayerConfig(synth.BF16, 512, 4, 128, 1024, 384, 2, tp_size=2, tp_rank=0,
                                     dropout_p=0.1, seed=0, layer_id=2),
     # multiples of 128 but not of 256: the smaller matrix-core tiles
-    "tiles128_bf16": synth.LayerConfig(synth.BF16, 640, 3, 128, 1152, 128, 3, tp_size=1,
+    "tiles128_bf16": synth.LayerConfig(synth.BF16, 640, 3, 128, 1152, 128, 3, tp_size=2, tp_rank=1,
                                        dropout_p=0.1, seed=4, layer_id=7),
     # sequence of two 256-tiles: the large score tiles and multi-slab causal contractions
     "tiles256_bf16": synth.LayerConfig(synth.BF16, 256, 2, 128, 256, 512, 1, tp_size=1,
