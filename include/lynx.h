@@ -190,8 +190,12 @@ lynx_status lynx_layer_set_dry_run(lynx_layer_t layer, int on);
  * calls).  lynx_layer_profile_ms blocks until the recorded events complete
  * and writes, per slot, the milliseconds of its most recent run since the
  * previous query, or -1 if it did not run.  Slots 1..13 are the forward
- * operators (slot 4 covers OP5 when the two run fused); the rest are the
- * backward kernels; lynx_profile_slot_name names them ("" when unused). */
+ * operators; an operator that ran inside the launch of the one before it has
+ * no time of its own (-1) and is covered by that slot: OP5 by slot 4, and,
+ * where the matrix-core kernels apply, OP8 by slot 7 and OP13 by slot 12.  The
+ * rest are the backward kernels (likewise the GeLU backward may run inside
+ * the FC2 gradient launch, and dPd with the softmax backward as one launch);
+ * lynx_profile_slot_name names them ("" when unused). */
 #define LYNX_PROFILE_SLOTS 40
 lynx_status lynx_layer_set_profiling(lynx_layer_t layer, int on);
 lynx_status lynx_layer_profile_ms(lynx_layer_t layer, float* ms_out /* [LYNX_PROFILE_SLOTS], host */);
