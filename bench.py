@@ -375,9 +375,12 @@ def main():
         # OP7+OP8 and OP12+OP13 run as one launch each where the matrix-core kernel applies (the
         # time is under the linear operator); run on its own, the bias + dropout + residual
         # operator moves 3 T h e bytes: price it at 5.5 TB/s, what the stand-alone kernel reaches
+        # (and take about two thirds of that off the fused launch: it does the same work minus a
+        # write and a read of the product)
         for lin in (7, 12):
             if cost[lin] == 0.0:
                 cost[lin] = 3.0 * cfg.tokens * cfg.hidden * (2 if cfg.dtype == 1 else 4) / 5.5e9
+                cost[lin - 1] = max(cost[lin - 1] - 0.65 * cost[lin], 0.5 * cost[lin - 1])
         M = [B.lynx_activation_bytes(cfg, i) for i in range(14)]
         budget = M[13] + args.budget_frac * sum(M[1:13])
         ctime = [float(v) for v in args.ctime_ms.split(",")]
