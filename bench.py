@@ -308,6 +308,9 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="also time the HBM-bound forward operators one by one after a 1 GiB read sweep "
                          "(cold caches) next to their in-situ figures")
+    ap.add_argument("--zeros", action="store_true",
+                    help="diagnostic: all-zero inputs and parameters (shows how far the dense products are "
+                         "held back by power rather than by their schedule); the line says data=zeros")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (the known-size kernel that "
@@ -342,6 +345,12 @@ def main():
     log("bench: config %s policy %s; generating inputs" % (args.config, policy))
     params = {k: dev(v) for k, v in synth.make_params(cfg).items()}
     x, dout = dev(synth.make_x(cfg)), dev(synth.make_dout(cfg))
+    if args.zeros:
+        # a diagnostic, not a benchmark line: the same launches on all-zero operands.  Nothing
+        # toggles in the matrix pipes, the clock stays up, and what the dense products then
+        # reach is the limit of their schedule rather than of the chip's power budget
+        for t in list(params.values()) + [x, dout]:
+            t.zero_()
     out, dx = torch.empty_like(x), torch.empty_like(x)
     grads = {k: torch.empty_like(v) for k, v in params.items()}
     ws_bytes = B.lynx_workspace_bytes(cfg, mask)
@@ -502,7 +511,8 @@ def main():
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(rb_ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == synth.BF16 else "f32", "data": "synthetic",
+        "dtype": "bf16" if cfg.dtype == synth.BF16 else "f32",
+        "data": "zeros (diagnostic, not a benchmark figure)" if args.zeros else "synthetic",
         "config": {"workload": "%s: h=%d a=%d d=%d f=%d s=%d b=%d tp=%d, policy=%s" % (
             args.config, cfg.hidden, cfg.local_heads, cfg.head_dim, cfg.local_ffn, cfg.seq,
             cfg.micro_batch, cfg.tp_size, policy),
