@@ -214,6 +214,31 @@ def test_dropout_scaling_and_mask_application():
     assert not acts["keep1"].all() and acts["keep1"].any()
 
 
+def test_softmax_backward_row_dot_is_dc_dot_c():
+    """The identity the GPU's one-pass dS kernel rests on: the row term of the softmax
+    backward, sum_j dP_ij P_ij with dP = keep c dPd and dPd = dC V^T, equals
+    sum_j dPd_ij Pd_ij = dC_i . (Pd V)_i = dC_i . C_i, for any dC.  Checked on the oracle's own
+    forward tensors (its backward forms the sum over j as written in the definition)."""
+    cfg = tiny_cfg(seq=12, micro_batch=2, dropout_p=0.25)
+    params, X, _ = f64_inputs(cfg)
+    acts = orc.layer_forward(cfg, params, X, step=2)
+    b, s, a, d = cfg.micro_batch, cfg.seq, cfg.local_heads, cfg.head_dim
+    p = a * d
+    c = 1 / (1 - 0.25)
+    rng = np.random.default_rng(3)
+    dC = rng.standard_normal((b * s, p))
+    for bi in range(b):
+        rows = slice(bi * s, (bi + 1) * s)
+        for hd in range(a):
+            v = acts["QKV"][rows, 2 * p + hd * d:2 * p + (hd + 1) * d]
+            dc = dC[rows, hd * d:(hd + 1) * d]
+            dP = acts["keep0"][bi, hd] * (dc @ v.T) * c
+            by_definition = (dP * acts["P"][bi, hd]).sum(axis=1)
+            from_context = (dc * acts["C"][rows, hd * d:(hd + 1) * d]).sum(axis=1)
+            assert np.allclose(by_definition, from_context, rtol=1e-12, atol=1e-13)
+    assert not acts["keep0"].all()      # the masks do drop something
+
+
 def _torch_block(cfg, params, X, masks):
     """The same block from library primitives, differentiated by autograd."""
     F = torch.nn.functional
