@@ -118,6 +118,16 @@ size_t lynx_activation_bytes(const lynx_layer_config* cfg, int act_id);
  * lynx_layer_peak_bytes.  0 on a bad config. */
 size_t lynx_workspace_bytes(const lynx_layer_config* cfg, uint32_t retain_mask);
 
+/* The same for a schedule with explicit regeneration phases (Sec. 4.2: the
+ * memory constraints, Eq. cons15-cons17, count what phases 1 and 2 bring back
+ * on top of what the forward pass retained): the sequence rehearsed is
+ * forward(retain_mask) -> recompute(phase_masks[0]) .. recompute(phase_masks[3])
+ * (zero entries skipped) -> backward.  phase_masks (host, 4 entries) may be NULL,
+ * which gives lynx_workspace_bytes.  Exact for that sequence; 0 on a bad config
+ * or when a phase names an operator whose input is absent at that point. */
+size_t lynx_workspace_bytes_for_schedule(const lynx_layer_config* cfg, uint32_t retain_mask,
+                                         const uint32_t* phase_masks);
+
 /* Create a layer over a caller-owned device workspace (borrowed until
  * destroy).  Errors: INVALID_ARG (null/misaligned), SHAPE. */
 lynx_status lynx_layer_create(const lynx_layer_config* cfg, void* workspace_device,
@@ -170,6 +180,19 @@ lynx_status lynx_layer_peak_bytes(lynx_layer_t layer, size_t* bytes);
  * statistics follow the [T, h] tensor directly: mean[T] then rstd[T], fp32. */
 lynx_status lynx_layer_activation(lynx_layer_t layer, int act_id, const void** device_ptr,
                                   size_t* bytes);
+
+/* Parity aid for the backward pass (Sec. 4.2 places no requirement on it: the
+ * method must leave every gradient unchanged, and this is how a test looks at
+ * the ones that never reach the caller).  While device_dst is set for act_id,
+ * every lynx_layer_backward also copies the gradient with respect to activation
+ * A_act_id, as its kernels formed it, to device_dst on the call's stream:
+ *   12 dV2 [T, h]   10 dU [T, f]   9 dY2 [T, h]   8 dX2 [T, h]   7 dO [T, h]
+ *   6 dC [T, a*d]   3 dS [b, a, s, s] (j <= i defined)   2 dQKV [T, 3*a*d]
+ *   1 dY1 [T, h]
+ * in the storage dtype; device_dst holds that many elements (dS: the whole
+ * dense [b, a, s, s] block is copied).  NULL clears the tap.
+ * Other act_id (gradients no kernel materialises) -> INVALID_ARG. */
+lynx_status lynx_layer_set_gradient_tap(lynx_layer_t layer, int act_id, void* device_dst);
 
 /* Write the keep-mask of one dropout site as bytes (1 = keep) for parity
  * checks: site 0 -> [b, a, s, s] (all j, also above the diagonal), sites 1, 2

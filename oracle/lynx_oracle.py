@@ -244,9 +244,12 @@ def layer_forward(cfg, params, X, step: int = 0) -> Dict[str, np.ndarray]:
     return out
 
 
-def layer_backward(cfg, params, acts, dOUT) -> Dict[str, np.ndarray]:
+def layer_backward(cfg, params, acts, dOUT, taps=None) -> Dict[str, np.ndarray]:
     """Backward of the block given the forward's activations and dL/dOUT.
-    Returns dX and the gradient of every parameter (same names as params)."""
+    Returns dX and the gradient of every parameter (same names as params).
+    If `taps` is a dict it also receives the gradients with respect to the
+    named activations as they are formed on the way down (dV2, dU, dY2, dX2,
+    dO, dC, dS, dQKV, dY1); nothing else changes."""
     w = _f64(params)
     dOUT = np.asarray(dOUT, dtype=np.float64)
     b, s, a, d = cfg.micro_batch, cfg.seq, cfg.local_heads, cfg.head_dim
@@ -297,6 +300,8 @@ def layer_backward(cfg, params, acts, dOUT) -> Dict[str, np.ndarray]:
             dS = dZ / math.sqrt(d)
             dQKV[rows, cq] = dS @ k                          # B3
             dQKV[rows, ck] = dS.T @ q
+            if taps is not None:
+                taps.setdefault("dS", np.zeros((b, a, s, s)))[bi, hd] = dS
     # B2: QKV = Y1 Wqkv^T + bqkv
     dY1 = dQKV @ w["wqkv"]
     g["wqkv"] = dQKV.T @ acts["Y1"]
@@ -304,6 +309,8 @@ def layer_backward(cfg, params, acts, dOUT) -> Dict[str, np.ndarray]:
     # B1: LayerNorm 1
     dx, g["g1"], g["be1"] = layernorm_bwd(dY1, acts["X"], acts["mu1"], acts["rstd1"], w["g1"])
     g["dX"] = dX + dx
+    if taps is not None:
+        taps.update(dV2=dV2, dU=dU, dY2=dY2, dX2=dX2, dO=dO, dC=dC, dQKV=dQKV, dY1=dY1)
     return g
 
 

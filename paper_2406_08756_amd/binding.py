@@ -77,6 +77,8 @@ _cfg_p = C.POINTER(lynx_layer_config)
 _proto = {
     "lynx_activation_bytes": (C.c_size_t, [_cfg_p, C.c_int]),
     "lynx_workspace_bytes": (C.c_size_t, [_cfg_p, C.c_uint32]),
+    "lynx_workspace_bytes_for_schedule": (C.c_size_t, [_cfg_p, C.c_uint32, C.POINTER(C.c_uint32)]),
+    "lynx_layer_set_gradient_tap": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "lynx_layer_create": (C.c_int, [_cfg_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]),
     "lynx_layer_destroy": (C.c_int, [C.c_void_p]),
     "lynx_layer_set_params": (C.c_int, [C.c_void_p, C.POINTER(lynx_params)]),
@@ -152,6 +154,15 @@ def lynx_activation_bytes(cfg, act_id: int) -> int:
 
 def lynx_workspace_bytes(cfg, retain_mask: int) -> int:
     return _lib.lynx_workspace_bytes(C.byref(make_config(cfg)), retain_mask)
+
+
+def lynx_workspace_bytes_for_schedule(cfg, retain_mask: int, phase_masks=None) -> int:
+    pm = None if phase_masks is None else (C.c_uint32 * 4)(*[int(m) for m in phase_masks])
+    return _lib.lynx_workspace_bytes_for_schedule(C.byref(make_config(cfg)), retain_mask, pm)
+
+
+def lynx_layer_set_gradient_tap(layer: int, act_id: int, dst) -> None:
+    _check(_lib.lynx_layer_set_gradient_tap(layer, act_id, _addr(dst)), "lynx_layer_set_gradient_tap")
 
 
 def lynx_layer_create(cfg, workspace, workspace_bytes: int) -> int:
@@ -306,28 +317,14 @@ def lynx_policy_solve(problem: dict):
     needed (sets of 1-based indices), ctime[4], m_budget, m_static, n_layer,
     n_batch, last_stage.  Returns a dict (retain_mask, phase_mask[5],
     critical_cost, recompute_cost, peak_bytes), or None when nothing fits."""
-    n = int(problem["n"])
-    cost = (C.c_double * n)(*[float(v) for v in problem["cost"]])
-    nbytes = (C.c_double * n)(*[float(v) for v in problem["bytes"]])
-    parents = (C.c_uint32 * n)(*[_mask_of(q) for q in problem["parents"]])
-    p = lynx_policy_problem()
-    p.n_ops = n
-    p.cost, p.bytes, p.parents = cost, nbytes, parents
-    p.comm_mask, p.needed_mask = _mask_of(problem["comm"]), _mask_of(problem["needed"])
-    for t in range(4):
-        p.ctime[t] = float(problem["ctime"][t])
-    p.m_budget, p.m_static = float(problem["m_budget"]), float(problem["m_static"])
-    p.n_layer, p.n_batch = int(problem["n_layer"]), int(problem["n_batch"])
-    p.last_stage = 1 if problem["last_stage"] else 0
+    p, keep = _policy_problem_struct(problem)
     out = lynx_policy()
     st = _lib.lynx_policy_solve(C.byref(p), C.byref(out))
     if st == LYNX_ERR_OOM:
         return None
     if st != LYNX_OK:
         raise LynxError(st, "lynx_policy_solve")
-    return {"retain_mask": int(out.retain_mask), "phase_mask": [int(m) for m in out.phase_mask],
-            "critical_cost": float(out.critical_cost), "recompute_cost": float(out.recompute_cost),
-            "peak_bytes": float(out.peak_bytes)}
+    return _policy_dict(out)
 
 
 def lynx_policy_layer_problem(cfg, cost, ctime, m_budget, m_static=0.0, n_layer=1, n_batch=1,

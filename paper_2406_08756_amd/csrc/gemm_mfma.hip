@@ -22,6 +22,7 @@
 // The product is formed transposed (B fragment as the first MFMA operand) so
 // each lane ends with four consecutive n of one row m; the epilogue passes the
 // tile through LDS and stores whole rows, 16 bytes per lane.
+#include <mutex>
 #include <type_traits>
 
 #include "dropout_host.h"
@@ -874,18 +875,24 @@ splitk_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C, 
   *reinterpret_cast<uint4*>(C + static_cast<long long>(m) * ldc + n) = o;
 }
 
+// Raises a kernel's dynamic LDS limit, once per call site (i.e. per kernel instantiation) and
+// safely when several host threads drive different layers at the same time.
+#define LYNX_RAISE_LDS_LIMIT(kern, smem)                                                        \
+  do {                                                                                          \
+    static std::once_flag once_;                                                                \
+    static hipError_t err_ = hipSuccess;                                                        \
+    std::call_once(once_, [&] {                                                                 \
+      err_ = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                           \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)); \
+    });                                                                                         \
+    if (err_ != hipSuccess) return err_;                                                        \
+  } while (0)
+
 template <bool AK, bool BK_, int BM, int BN>
 hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
   constexpr size_t smem = static_cast<size_t>(kStages) * (BM + BN) * kBK * sizeof(bf16_t);
   auto kern = gemm_mfma_kernel<AK, BK_, BM, BN>;
-  static bool configured = false;  // raise the dynamic LDS limit once per instantiation
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(smem));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  LYNX_RAISE_LDS_LIMIT(kern, smem);
   const int ntiles = a.causal == kCausalOutLower ? a.tiles_m * (a.tiles_m + 1) / 2 : a.tiles_m * a.tiles_n;
   const bool flat = a.causal == kCausalKLeM || a.causal == kCausalKGeM;  // (tile, matrix) in x
   hipLaunchKernelGGL(kern, flat ? dim3(ntiles * a.nz) : dim3(ntiles, a.nz), dim3(kThreads), smem, st, a);
@@ -896,14 +903,7 @@ template <bool AK, bool BK_>
 hipError_t launch_edge(const MfmaGemmArgs& a, hipStream_t st) {
   constexpr size_t smem = static_cast<size_t>(kStages) * (256 + 256) * kBK * sizeof(bf16_t);
   auto kern = gemm_mfma_edge_kernel<AK, BK_>;
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(smem));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  LYNX_RAISE_LDS_LIMIT(kern, smem);
   MfmaGemmArgs body = a, edge = a;
   const int n_body_cols = a.N - 128;
   body.N = n_body_cols;
@@ -923,14 +923,7 @@ template <int KD>
 hipError_t launch_attn_outer(MfmaGemmArgs a, hipStream_t st) {
   constexpr size_t smem = (3 * static_cast<size_t>(KD / kBK) * 128 * kBK + 4 * 64 * 64) * sizeof(bf16_t);
   auto kern = attn_outer_kernel<KD>;
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(smem));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  LYNX_RAISE_LDS_LIMIT(kern, smem);
   a.tiles_m = a.M / 128;
   a.tiles_n = a.N / 128;
   hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.nz), dim3(kThreads), smem, st, a);
@@ -941,14 +934,7 @@ template <int KD>
 hipError_t launch_attn_dscores(MfmaGemmArgs a, hipStream_t st) {
   constexpr size_t smem = 2 * static_cast<size_t>(KD / kBK) * 128 * kBK * sizeof(bf16_t);
   auto kern = attn_dscores_kernel<KD>;
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(smem));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  LYNX_RAISE_LDS_LIMIT(kern, smem);
   a.tiles_m = a.M / 128;
   a.tiles_n = a.N / 128;
   hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.nz), dim3(kThreads), smem, st, a);
@@ -1049,14 +1035,7 @@ hipError_t launch_pair(MfmaGemmArgs w, MfmaGemmArgs d, const PairPlan& plan, hip
   constexpr int dsum = DBM + DBN, wsum = WBM + WBN;
   constexpr size_t smem = static_cast<size_t>(kStages) * (dsum > wsum ? dsum : wsum) * kBK * sizeof(bf16_t);
   auto kern = gemm_mfma_pair_kernel<DBM, DBN, WBM, WBN, EBM, EBN>;
-  static bool configured = false;
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(smem));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  LYNX_RAISE_LDS_LIMIT(kern, smem);
   // the edge strip: the same product restricted to the last 128 rows or columns of dW
   MfmaGemmArgs e = w;
   int n_e = 0;
@@ -1196,8 +1175,12 @@ hipError_t gemm_mfma_pair(const GemmDesc& dgrad, const GemmDesc& wgrad, float* s
   const MfmaGemmArgs d = make_args(dgrad);
   MfmaGemmArgs w = make_args(wgrad);
   const PairPlan p = plan_pair(w.M, w.N, w.K, d.M, d.N, d.K);
-  if (p.k_splits > 1 && scratch != nullptr && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0 &&
-      scratch_bytes >= static_cast<size_t>(p.k_splits) * w.M * w.N * sizeof(float)) {
+  if (p.k_splits > 1) {
+    // The cut is part of the shape's fixed summation order: a scratch block that cannot hold
+    // the partial sums is an error, never a silent change of the gradient's bits.
+    if (scratch == nullptr || (reinterpret_cast<uintptr_t>(scratch) & 15) != 0 ||
+        scratch_bytes < static_cast<size_t>(p.k_splits) * w.M * w.N * sizeof(float))
+      return hipErrorInvalidValue;
     w.k_splits = p.k_splits;
     w.partial = scratch;
   }

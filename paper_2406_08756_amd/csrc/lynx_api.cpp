@@ -107,6 +107,8 @@ struct lynx_layer_s {
   hipEvent_t ev_begin[LYNX_PROFILE_SLOTS] = {};
   hipEvent_t ev_end[LYNX_PROFILE_SLOTS] = {};
   bool ev_recorded[LYNX_PROFILE_SLOTS] = {};
+  // parity aid: where backward copies the gradient with respect to activation A_i (null: nowhere)
+  void* grad_tap[LYNX_NUM_ACTIVATIONS] = {};
 };
 
 namespace {
@@ -190,6 +192,20 @@ void free_temp(Ctx& cx, Temp* t) {
   t->held = false;
 }
 char* temp_ptr(const Ctx& cx, const Temp& t) { return cx.L->base + t.off; }
+
+// Gradients a tap may name, and their sizes: those every kernel path materialises.
+constexpr uint32_t kTappable = (1u << 12) | (1u << 10) | (1u << 9) | (1u << 8) | (1u << 7) | (1u << 6) |
+                               (1u << 3) | (1u << 2) | (1u << 1);
+size_t tap_bytes(const Dims& D, int i) {
+  return (i == 1 || i == 9) ? static_cast<size_t>(D.T) * D.h * D.e : act_bytes(D, i);
+}
+lynx_status tap(Ctx& cx, int i, const void* grad) {
+  void* dst = cx.L->grad_tap[i];
+  if (!cx.launch || dst == nullptr) return LYNX_OK;
+  const hipError_t e = hipMemcpyAsync(dst, grad, tap_bytes(cx.L->D, i), hipMemcpyDeviceToDevice, cx.st);
+  if (e != hipSuccess) { cx.hip = e; return LYNX_ERR_HIP; }
+  return LYNX_OK;
+}
 
 lynx::DropoutParams dropout_params(const lynx_layer_s* L) {
   return lynx::DropoutParams{L->cfg.seed, L->step, L->cfg.layer_id, L->cfg.dropout_p};
@@ -523,6 +539,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_TRY(alloc_temp(cx, th, &t_dv2));
   LYNX_LAUNCH(cx, kB13Dropout, lynx::dropout_bwd(dt, d_out, temp_ptr(cx, t_dv2), gr->b2, scr, D.T, D.h, 2,
                                     dropout_params(L), cx.st));
+  LYNX_TRY(tap(cx, 12, temp_ptr(cx, t_dv2)));
   // B12: V2 = G W2^T, and B11: G = gelu(U).  When the matrix-core pair launch applies, the
   // store pass of the input gradient multiplies by gelu'(U) and sums the columns (the FC1
   // bias gradient), so dG is never written and the GeLU backward never runs as a kernel.
@@ -556,11 +573,13 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
     }
   }
   free_act(cx, 10);
+  LYNX_TRY(tap(cx, 10, temp_ptr(cx, t_du)));
   // B10: U = Y2 W1^T + b1
   LYNX_TRY(alloc_temp(cx, th, &t_dy2));
   LYNX_LAUNCH(cx, kB10Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_du), w.w1, temp_ptr(cx, t_dy2), D.T, D.f, D.h),
                                                   linear_wgrad(temp_ptr(cx, t_du), act_ptr(cx, 9), gr->w1, D.T, D.f, D.h), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_du);
+  LYNX_TRY(tap(cx, 9, temp_ptr(cx, t_dy2)));
   // B9: Y2 = LN2(X2); dX2 = dOUT + dLN.  B8 in the same pass: X2 = X + keep1 (O + bo) c,
   // so dO = keep1 c dX2 and dbo = its column sums
   LYNX_TRY(alloc_temp(cx, th, &t_dx2));
@@ -570,6 +589,8 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
                                               stats_ptr(cx, 9) + D.T, w.g2, d_out, temp_ptr(cx, t_dx2), gr->g2,
                                               gr->be2, temp_ptr(cx, t_do), gr->bo, scr, D.T, D.h, 1,
                                               dropout_params(L), cx.st));
+  LYNX_TRY(tap(cx, 8, temp_ptr(cx, t_dx2)));
+  LYNX_TRY(tap(cx, 7, temp_ptr(cx, t_do)));
   free_temp(cx, &t_dy2);
   free_act(cx, 9);
   free_act(cx, 8);
@@ -578,6 +599,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_LAUNCH(cx, kB7Grads, lynx::gemm_pair(dt, linear_dgrad(temp_ptr(cx, t_do), w.wo, temp_ptr(cx, t_dc), D.T, D.h, D.p),
                                                   linear_wgrad(temp_ptr(cx, t_do), act_ptr(cx, 6), gr->wo, D.T, D.h, D.p), scr, scratch_bytes, cx.st));
   free_temp(cx, &t_do);
+  LYNX_TRY(tap(cx, 6, temp_ptr(cx, t_dc)));
   // B6: C = Pd V (C itself is read once more below, for the row dot products)
   LYNX_TRY(alloc_temp(cx, D.ss * e, &t_dpd));
   LYNX_TRY(alloc_temp(cx, static_cast<size_t>(D.T) * 3 * D.p * e, &t_dqkv));
@@ -622,6 +644,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
                                               cx.st));
   }
   free_act(cx, 4);
+  LYNX_TRY(tap(cx, 3, temp_ptr(cx, t_dpd)));
   // B3: S = Q K^T
   LYNX_LAUNCH(cx, kB3DQ, lynx::gemm(dt, attn_rows(temp_ptr(cx, t_dpd), col_block(qkv, D, 1), 3 * D.p,
                                            const_cast<char*>(col_block(dqkv, D, 0)), 3 * D.p, D),
@@ -631,6 +654,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
                              cx.st));
   free_temp(cx, &t_dpd);
   free_act(cx, 3);
+  LYNX_TRY(tap(cx, 2, dqkv));
   // B2: QKV = Y1 Wqkv^T + bqkv
   LYNX_TRY(alloc_temp(cx, th, &t_dy1));
   LYNX_LAUNCH(cx, kB2Grads, lynx::gemm_pair(dt, linear_dgrad(dqkv, w.wqkv, temp_ptr(cx, t_dy1), D.T, 3 * D.p, D.h),
@@ -638,6 +662,7 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   LYNX_LAUNCH(cx, kB2BiasGrad, lynx::column_sum(dt, dqkv, gr->bqkv, scr, D.T, 3 * D.p, cx.st));
   free_temp(cx, &t_dqkv);
   free_act(cx, 2);
+  LYNX_TRY(tap(cx, 1, temp_ptr(cx, t_dy1)));
   // B1: Y1 = LN1(X); dX = dX2 + dLN
   LYNX_LAUNCH(cx, kB1LayerNorm, lynx::layernorm_bwd(dt, temp_ptr(cx, t_dy1), act_ptr(cx, 0), stats_ptr(cx, 1),
                                       stats_ptr(cx, 1) + D.T, w.g1, temp_ptr(cx, t_dx2), d_x, gr->g1,
@@ -796,7 +821,8 @@ lynx_status lynx_layer_activation(lynx_layer_t L, int act_id, const void** devic
   return LYNX_OK;
 }
 
-size_t lynx_workspace_bytes(const lynx_layer_config* cfg, uint32_t retain_mask) {
+size_t lynx_workspace_bytes_for_schedule(const lynx_layer_config* cfg, uint32_t retain_mask,
+                                         const uint32_t* phase_masks) {
   Dims D;
   if (!make_dims(cfg, &D) || (retain_mask & ~0x3FFFu)) return 0;
   lynx_layer_s L;
@@ -805,10 +831,22 @@ size_t lynx_workspace_bytes(const lynx_layer_config* cfg, uint32_t retain_mask) 
   L.base = nullptr;
   L.book.arena = Arena(static_cast<size_t>(1) << 60);
   Ctx cx{&L, &L.book, false, nullptr};
-  lynx_grads g{};
+  // Nothing is launched; the placeholders only have to look like what a real call passes
+  // (non-null, aligned), so that the rehearsal takes the kernel path a real call takes.
+  void* const fake = reinterpret_cast<void*>(static_cast<uintptr_t>(Arena::kAlign));
+  const lynx_grads g{fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake};
+  L.params = lynx_params{fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake};
+  L.x = fake;
+  L.out = fake;
   if (forward_pass(cx, retain_mask) != LYNX_OK) return 0;
-  if (backward_pass(cx, nullptr, nullptr, &g) != LYNX_OK) return 0;
+  for (int t = 0; phase_masks != nullptr && t < 4; ++t)
+    if (phase_masks[t] != 0 && recompute_pass(cx, phase_masks[t]) != LYNX_OK) return 0;
+  if (backward_pass(cx, fake, fake, &g) != LYNX_OK) return 0;
   return L.book.arena.extent_peak();
+}
+
+size_t lynx_workspace_bytes(const lynx_layer_config* cfg, uint32_t retain_mask) {
+  return lynx_workspace_bytes_for_schedule(cfg, retain_mask, nullptr);
 }
 
 lynx_status lynx_dropout_mask(const lynx_layer_config* cfg, uint64_t step, int site, uint8_t* out,
@@ -826,6 +864,14 @@ lynx_status lynx_dropout_mask(const lynx_layer_config* cfg, uint64_t step, int s
   else
     e = lynx::dropout_mask_hidden(out, static_cast<size_t>(D.T) * D.h, site, dp, st);
   return e == hipSuccess ? LYNX_OK : LYNX_ERR_HIP;
+}
+
+lynx_status lynx_layer_set_gradient_tap(lynx_layer_t L, int act_id, void* device_dst) {
+  if (L == nullptr || act_id < 0 || act_id >= kNumAct || !((kTappable >> act_id) & 1u))
+    return LYNX_ERR_INVALID_ARG;
+  if (device_dst != nullptr && !aligned16(device_dst)) return LYNX_ERR_INVALID_ARG;
+  L->grad_tap[act_id] = device_dst;
+  return LYNX_OK;
 }
 
 lynx_status lynx_layer_set_profiling(lynx_layer_t L, int on) {

@@ -87,6 +87,23 @@ class GpuLayer:
             shp = shapes.get(act_id, (cfg.tokens, cfg.hidden))
         return to_host(raw).reshape(shp)
 
+    TAP_IDS = {"dV2": 12, "dU": 10, "dY2": 9, "dX2": 8, "dO": 7, "dC": 6, "dS": 3, "dQKV": 2, "dY1": 1}
+
+    def tap_gradients(self, names):
+        """Have the following backward calls copy the named intermediate gradients out."""
+        cfg = self.cfg
+        e = 2 if cfg.dtype == synth.BF16 else 4
+        self.taps = {}
+        for name in names:
+            act = self.TAP_IDS[name]
+            n = self.B.lynx_activation_bytes(cfg, act)
+            if act in (1, 9):
+                n = cfg.tokens * cfg.hidden * e
+            buf = torch.empty(n // e, dtype=self.tdtype, device="cuda")
+            self.B.lynx_layer_set_gradient_tap(self.handle, act, buf)
+            self.taps[name] = buf
+        return self.taps
+
     def stats(self, act_id):
         """(mean, rstd) stored behind Y1 (act 1) or Y2 (act 9)."""
         addr, nbytes = self.B.lynx_layer_activation(self.handle, act_id)
