@@ -134,6 +134,24 @@ lynx_status lynx_layer_create(const lynx_layer_config* cfg, void* workspace_devi
                               size_t workspace_bytes, lynx_layer_t* out_layer);
 lynx_status lynx_layer_destroy(lynx_layer_t layer);
 
+/* lynx_layer_create for callers that cannot allocate device memory (code under
+ * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the
+ * layer's workspace is a block of LYNX_STATIC_WORKSPACE_BYTES that is part of
+ * the library's code object, so neither this call nor any later call on the
+ * handle calls an allocation routine.  Each GPU has its own copy of the block,
+ * held until the process ends; the layer uses the copy of the device that is
+ * current at this call.  Everything else is lynx_layer_create: same kernels,
+ * same bits.  The block keeps whatever the previous layer left in it (no
+ * kernel reads workspace memory it has not written), and one layer at a time
+ * may live in it per GPU: two would overwrite each other, so a second create on
+ * the same device before the first is destroyed fails with STATE.  Errors:
+ * INVALID_ARG, SHAPE, OOM when even the leanest schedule of this shape
+ * (lynx_workspace_bytes(cfg, LYNX_RETAIN_FULL_RECOMPUTE)) exceeds the block -
+ * later calls return OOM as usual when a richer retain mask does not fit -,
+ * HIP when the block's address cannot be obtained. */
+#define LYNX_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+lynx_status lynx_layer_create_static(const lynx_layer_config* cfg, lynx_layer_t* out_layer);
+
 lynx_status lynx_layer_set_params(lynx_layer_t layer, const lynx_params* params);
 
 /* Forward pass (operators 1..13) under a retain policy: after an operator's

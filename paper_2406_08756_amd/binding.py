@@ -30,6 +30,7 @@ LYNX_RETAIN_ELEMENTWISE_ONLY = 0x3FFF & ~0x0830
 LYNX_SEG_ALL_MISSING = 0xFFFFFFFF
 LYNX_NUM_ACTIVATIONS = 14
 LYNX_PROFILE_SLOTS = 40
+LYNX_STATIC_WORKSPACE_BYTES = 64 << 20
 PARAM_FIELDS = ("wqkv", "bqkv", "wo", "bo", "w1", "b1", "w2", "b2", "g1", "be1", "g2", "be2")
 
 
@@ -80,6 +81,7 @@ _proto = {
     "lynx_workspace_bytes_for_schedule": (C.c_size_t, [_cfg_p, C.c_uint32, C.POINTER(C.c_uint32)]),
     "lynx_layer_set_gradient_tap": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "lynx_layer_create": (C.c_int, [_cfg_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]),
+    "lynx_layer_create_static": (C.c_int, [_cfg_p, C.POINTER(C.c_void_p)]),
     "lynx_layer_destroy": (C.c_int, [C.c_void_p]),
     "lynx_layer_set_params": (C.c_int, [C.c_void_p, C.POINTER(lynx_params)]),
     "lynx_layer_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
@@ -169,6 +171,12 @@ def lynx_layer_create(cfg, workspace, workspace_bytes: int) -> int:
     handle = C.c_void_p()
     _check(_lib.lynx_layer_create(C.byref(make_config(cfg)), _addr(workspace), workspace_bytes,
                                   C.byref(handle)), "lynx_layer_create")
+    return handle.value
+
+
+def lynx_layer_create_static(cfg) -> int:
+    handle = C.c_void_p()
+    _check(_lib.lynx_layer_create_static(C.byref(make_config(cfg)), C.byref(handle)), "lynx_layer_create_static")
     return handle.value
 
 

@@ -16,6 +16,7 @@
 #include "../../include/lynx.h"
 #include "arena.h"
 #include "kernels.h"
+#include "static_workspace.h"
 
 namespace {
 
@@ -109,6 +110,7 @@ struct lynx_layer_s {
   bool ev_recorded[LYNX_PROFILE_SLOTS] = {};
   // parity aid: where backward copies the gradient with respect to activation A_i (null: nowhere)
   void* grad_tap[LYNX_NUM_ACTIVATIONS] = {};
+  int static_device = -1;  // >= 0: the workspace is that device's built-in block
 };
 
 namespace {
@@ -147,6 +149,7 @@ enum BackwardSlot {
   kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kB6RowDot, kB654DScores, kNumSlots
 };
 static_assert(kNumSlots <= LYNX_PROFILE_SLOTS, "profile slots");
+static_assert(LYNX_STATIC_WORKSPACE_BYTES == lynx::kStaticWorkspaceBytes, "header and library agree on the block size");
 const char* const kSlotNames[kNumSlots] = {
     "", "op1_layernorm1", "op2_qkv_gemm", "op3_scores", "op4_softmax_dropout", "op5_attn_dropout",
     "op6_context", "op7_attn_proj_gemm", "op8_bias_dropout_add1", "op9_layernorm2", "op10_fc1_gemm",
@@ -723,9 +726,35 @@ lynx_status lynx_layer_create(const lynx_layer_config* cfg, void* workspace, siz
   return LYNX_OK;
 }
 
+lynx_status lynx_layer_create_static(const lynx_layer_config* cfg, lynx_layer_t* out_layer) {
+  if (cfg == nullptr || out_layer == nullptr) return LYNX_ERR_INVALID_ARG;
+  Dims D;
+  if (!make_dims(cfg, &D)) return LYNX_ERR_SHAPE;
+  // the leanest schedule of this shape (keep the input only) must fit the block
+  const size_t least = lynx_workspace_bytes(cfg, LYNX_RETAIN_FULL_RECOMPUTE);
+  if (least == 0 || least > lynx::kStaticWorkspaceBytes) return LYNX_ERR_OOM;
+  lynx_layer_s* L = new (std::nothrow) lynx_layer_s;
+  if (L == nullptr) return LYNX_ERR_OOM;
+  void* base = nullptr;
+  int device = -1;
+  const hipError_t e = lynx::static_workspace_acquire(&base, &device);
+  if (e != hipSuccess) {
+    delete L;
+    return e == hipErrorContextAlreadyInUse ? LYNX_ERR_STATE : LYNX_ERR_HIP;
+  }
+  L->cfg = *cfg;
+  L->D = D;
+  L->base = static_cast<char*>(base);
+  L->book.arena = Arena(lynx::kStaticWorkspaceBytes);
+  L->static_device = device;
+  *out_layer = L;
+  return LYNX_OK;
+}
+
 lynx_status lynx_layer_destroy(lynx_layer_t layer) {
   if (layer == nullptr) return LYNX_ERR_INVALID_ARG;
   (void)lynx_layer_set_profiling(layer, 0);
+  if (layer->static_device >= 0) lynx::static_workspace_release(layer->static_device);
   delete layer;
   return LYNX_OK;
 }

@@ -23,17 +23,23 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 
 class GpuLayer:
-    def __init__(self, cfg: synth.LayerConfig, params, retain_mask_for_size=None, workspace_bytes=None):
+    def __init__(self, cfg: synth.LayerConfig, params, retain_mask_for_size=None, workspace_bytes=None,
+                 static_workspace=False):
         from paper_2406_08756_amd import binding as B
         self.B, self.cfg = B, cfg
         self.tdtype = torch.bfloat16 if cfg.dtype == synth.BF16 else torch.float32
-        if workspace_bytes is None:
-            mask = B.LYNX_RETAIN_STORE_ALL if retain_mask_for_size is None else retain_mask_for_size
-            workspace_bytes = B.lynx_workspace_bytes(cfg, mask)
-        self.workspace = torch.empty(workspace_bytes + 256, dtype=torch.uint8, device="cuda")
-        base = self.workspace.data_ptr()
-        self.ws_base = (base + 255) // 256 * 256
-        self.handle = B.lynx_layer_create(cfg, self.ws_base, workspace_bytes)
+        if static_workspace:
+            # the library's built-in block: activations cannot be read back through this class
+            self.workspace = None
+            self.handle = B.lynx_layer_create_static(cfg)
+        else:
+            if workspace_bytes is None:
+                mask = B.LYNX_RETAIN_STORE_ALL if retain_mask_for_size is None else retain_mask_for_size
+                workspace_bytes = B.lynx_workspace_bytes(cfg, mask)
+            self.workspace = torch.empty(workspace_bytes + 256, dtype=torch.uint8, device="cuda")
+            base = self.workspace.data_ptr()
+            self.ws_base = (base + 255) // 256 * 256
+            self.handle = B.lynx_layer_create(cfg, self.ws_base, workspace_bytes)
         self.params = {k: to_device(v, cfg.dtype) for k, v in params.items()}
         B.lynx_layer_set_params(self.handle, self.params)
         T, h = cfg.tokens, cfg.hidden
