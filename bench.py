@@ -70,17 +70,29 @@ def slot_work(cfg):
     }
 
 
+def regenerated_ops(cfg, retain_mask):
+    """The operators the library regenerates after a forward under retain_mask: asked of the
+    library itself, on a handle in dry-run mode (bookkeeping only, nothing is launched and the
+    placeholder addresses are never dereferenced)."""
+    from paper_2406_08756_amd import binding as B
+    fake = 256
+    h = B.lynx_layer_create(cfg, fake, 1 << 60)
+    B.lynx_layer_set_dry_run(h, True)
+    B.lynx_layer_set_params(h, {k: fake for k in B.PARAM_FIELDS})
+    B.lynx_layer_forward(h, fake, fake, retain_mask, 0)
+    m = B.lynx_layer_missing_mask(h)
+    B.lynx_layer_destroy(h)
+    return [i for i in range(1, 14) if (m >> i) & 1]
+
+
 def phase_flops(cfg, retain_mask):
     """Algorithmic matrix-product FLOPs of forward, of the regeneration the
     policy needs, and of backward."""
-    from oracle import policy_model as pm   # bookkeeping model only (no numerics)
     w = slot_work(cfg)
     op_slot = {2: "op2_qkv_gemm", 3: "op3_scores", 6: "op6_context", 7: "op7_attn_proj_gemm",
                10: "op10_fc1_gemm", 12: "op12_fc2_gemm"}
     fwd = sum(w[n][1] for n in op_slot.values())
-    bk = pm.LayerBookkeeping(cfg)
-    bk.forward(retain_mask)
-    rec = sum(w[op_slot[i]][1] for i in bk.recompute(pm.SEG_ALL_MISSING) if i in op_slot)
+    rec = sum(w[op_slot[i]][1] for i in regenerated_ops(cfg, retain_mask) if i in op_slot)
     bwd = sum(v for n, (kind, v) in w.items() if n.startswith("b") and kind == "mfma")
     return fwd, rec, bwd
 
@@ -407,7 +419,7 @@ def main():
                    phase_ops=[[i for i in range(1, 14) if (m >> i) & 1] for m in heu["phase_mask"]])
         log("bench: HEU policy retain 0x%04x phases %s critical %.3f ms of %.3f ms regenerated" % (
             mask, heu["phase_ops"], heu["critical_cost"], heu["recompute_cost"]))
-        ws_bytes = max(ws_bytes, 2 * B.lynx_workspace_bytes(cfg, mask))   # several segments: not the canonical sequence
+        ws_bytes = B.lynx_workspace_bytes_for_schedule(cfg, mask, heu["phase_mask"][:4])
         B.lynx_layer_destroy(layer)
         ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
         layer = B.lynx_layer_create(cfg, (ws.data_ptr() + 255) // 256 * 256, ws_bytes)

@@ -157,13 +157,14 @@ def test_masks_inside_the_standalone_dropout_kernels(name):
     cfg = SMALL[name]
     params = synth.make_params(cfg, random_ln=True)
     X = synth.make_x(cfg)
-    B = GpuLayer(cfg, params).B
-    layer = GpuLayer(cfg, params, workspace_bytes=2 * B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
+    from paper_2406_08756_amd import binding as B
     retain = pm.FULL_RECOMPUTE | (1 << 4) | (1 << 7) | (1 << 12)   # keep P, O and V2; drop Pd, X2
+    phases = [(1 << 1) | (1 << 2), 1 << 5, 1 << 8, 0]
+    layer = GpuLayer(cfg, params, workspace_bytes=B.lynx_workspace_bytes_for_schedule(cfg, retain, phases))
     layer.forward(X, retain, step=STEP)
-    layer.recompute((1 << 1) | (1 << 2))
-    layer.recompute(1 << 5)                      # attn_dropout_fwd from the resident P
-    layer.recompute(1 << 8)                      # bias_dropout_add from the resident O
+    layer.recompute(phases[0])
+    layer.recompute(phases[1])                   # attn_dropout_fwd from the resident P
+    layer.recompute(phases[2])                   # bias_dropout_add from the resident O
     torch.cuda.synchronize()
     live = B.lynx_layer_live_mask(layer.handle)
     assert (live >> 5) & 1 and (live >> 8) & 1 and (live >> 4) & 1 and (live >> 7) & 1

@@ -121,8 +121,12 @@ def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
     cfg = SMALL[name]
     params = synth.make_params(cfg, random_ln=True)
     X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
-    layer = GpuLayer(cfg, params, workspace_bytes=2 * GpuLayer(cfg, params).B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
-    B = layer.B
+    from paper_2406_08756_amd import binding as B
+    rng = np.random.default_rng(17)
+    masks = [pm.FULL_RECOMPUTE, pm.ATTENTION_ONLY, pm.ELEMENTWISE_ONLY, 1]
+    masks += [int(m) | 1 for m in rng.integers(0, 1 << 14, size=12)]
+    # every run starts from an empty workspace, so the exact size per mask applies to each
+    layer = GpuLayer(cfg, params, workspace_bytes=max(B.lynx_workspace_bytes(cfg, m) for m in [pm.STORE_ALL] + masks))
 
     def lower(i, t):
         if i in (3, 4, 5):
@@ -140,9 +144,6 @@ def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
     ref_dx = layer.dx.clone()
     ref_grads = {k: v.clone() for k, v in layer.grads.items()}
 
-    rng = np.random.default_rng(17)
-    masks = [pm.FULL_RECOMPUTE, pm.ATTENTION_ONLY, pm.ELEMENTWISE_ONLY, 1]
-    masks += [int(m) | 1 for m in rng.integers(0, 1 << 14, size=12)]
     for n, mask in enumerate(masks):
         layer.out.zero_(); layer.dx.zero_()
         for v in layer.grads.values():
@@ -177,8 +178,11 @@ def test_explicit_segments_in_phases_then_backward():
     cfg = SMALL["tiles_bf16"]
     params = synth.make_params(cfg, random_ln=True)
     X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
-    layer = GpuLayer(cfg, params, workspace_bytes=2 * GpuLayer(cfg, params).B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
-    B = layer.B
+    from paper_2406_08756_amd import binding as B
+    phases = [(1 << 1) | (1 << 2), (1 << 3) | (1 << 4), 1 << 5, (1 << 6) | (1 << 7) | (1 << 8)]
+    need = max(B.lynx_workspace_bytes(cfg, pm.STORE_ALL),
+               B.lynx_workspace_bytes_for_schedule(cfg, pm.FULL_RECOMPUTE, phases))
+    layer = GpuLayer(cfg, params, workspace_bytes=need)
     layer.forward(X, pm.STORE_ALL)
     layer.backward(dOUT)
     torch.cuda.synchronize()
@@ -188,11 +192,12 @@ def test_explicit_segments_in_phases_then_backward():
     with pytest.raises(B.LynxError) as e:
         layer.recompute(1 << 6)
     assert e.value.status == B.LYNX_ERR_DEPENDENCY
-    layer.recompute((1 << 1) | (1 << 2))            # "phase 1"
-    layer.recompute((1 << 3) | (1 << 4))            # "phase 2": P alone, S dropped again
+    layer.recompute(phases[0])                      # "phase 1"
+    layer.recompute(phases[1])                      # "phase 2": P alone, S dropped again
     assert not (B.lynx_layer_live_mask(layer.handle) >> 3) & 1
-    layer.recompute(1 << 5)                         # "phase 3": Pd from the resident P
-    layer.recompute((1 << 6) | (1 << 7) | (1 << 8)) # "phase 4"
+    layer.recompute(phases[2])                      # "phase 3": Pd from the resident P
+    layer.recompute(phases[3])                      # "phase 4"
+    assert B.lynx_layer_peak_bytes(layer.handle) <= need
     layer.backward(dOUT)                            # phase 5: the rest on demand
     torch.cuda.synchronize()
     assert torch.equal(layer.dx, ref_dx)
@@ -209,16 +214,10 @@ def test_solved_policies_run_through_the_layer():
     cfg = SMALL["tiles_bf16"]
     params = synth.make_params(cfg, random_ln=True)
     X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
-    layer = GpuLayer(cfg, params, workspace_bytes=2 * GpuLayer(cfg, params).B.lynx_workspace_bytes(cfg, pm.STORE_ALL))
-    B = layer.B
-    layer.forward(X, pm.STORE_ALL)
-    layer.backward(dOUT)
-    torch.cuda.synchronize()
-    ref_dx = layer.dx.clone()
-    ref_grads = {k: v.clone() for k, v in layer.grads.items()}
+    from paper_2406_08756_amd import binding as B
     M = pm.activation_bytes(cfg)
     cost = [1.0, 6.0, 1.5, 1.2, 0.0, 1.5, 2.0, 1.0, 1.0, 8.0, 0.5, 8.0, 1.0]
-    seen = set()
+    policies = []
     for frac, ctime in [(0.0, [0, 0, 0, 0]), (0.0, [0, 0, 4.0, 9.0]), (0.3, [2.0, 2.0, 3.0, 3.0]),
                         (0.6, [0, 0, 2.0, 2.0]), (0.15, [8.0, 0, 0, 8.0]), (0.5, [3.0, 3.0, 0, 0]),
                         (1.0, [0, 0, 0, 0])]:
@@ -226,6 +225,18 @@ def test_solved_policies_run_through_the_layer():
         prob = B.lynx_policy_layer_problem(cfg, cost, ctime=ctime, m_budget=budget + 1.0)
         pol = B.lynx_policy_solve(prob)
         assert pol is not None
+        policies.append(pol)
+    # the workspace each schedule needs, exactly (Eq. cons15-17 count the same things)
+    need = [B.lynx_workspace_bytes_for_schedule(cfg, q["retain_mask"], q["phase_mask"][:4]) for q in policies]
+    assert all(n > 0 for n in need)
+    layer = GpuLayer(cfg, params, workspace_bytes=max(need + [B.lynx_workspace_bytes(cfg, pm.STORE_ALL)]))
+    layer.forward(X, pm.STORE_ALL)
+    layer.backward(dOUT)
+    torch.cuda.synchronize()
+    ref_dx = layer.dx.clone()
+    ref_grads = {k: v.clone() for k, v in layer.grads.items()}
+    seen = set()
+    for pol in policies:
         seen.add((pol["retain_mask"], tuple(pol["phase_mask"])))
         layer.dx.zero_()
         for v in layer.grads.values():
@@ -257,6 +268,56 @@ def test_zero_output_projections_make_layer_identity_on_gpu():
     got = layer.results()
     assert np.array_equal(layer.out.float().cpu().numpy(), X)
     assert np.array_equal(got["dX"], dOUT.astype(np.float64))
+    layer.close()
+
+
+@pytest.mark.parametrize("name", ["tiles_bf16", "C4"])
+def test_regeneration_on_a_side_stream_under_the_comm_standin_keeps_the_bits(name):
+    """The paper's mechanism at one-GPU fidelity (Sec. 4, phases 1-4; Eq. cons13): the
+    regeneration segments run on a side stream while a stand-in for the tensor-parallel
+    all-reduce (a bounded-width copy) occupies the main stream; backward then waits for the
+    side stream.  Nothing about the results may change: same activations, same gradients
+    as the single-stream run."""
+    from paper_2406_08756_amd import binding as B
+    cfg = SMALL[name] if name in SMALL else synth.CONFIGS[name]
+    params = synth.make_params(cfg, random_ln=True)
+    X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
+    phases = [(1 << 1) | (1 << 2) | (1 << 3) | (1 << 4) | (1 << 5), (1 << 6) | (1 << 7) | (1 << 8), 1 << 9,
+              (1 << 10) | (1 << 11)]
+    need = max(B.lynx_workspace_bytes(cfg, pm.FULL_RECOMPUTE),
+               B.lynx_workspace_bytes_for_schedule(cfg, pm.FULL_RECOMPUTE, phases))
+    layer = GpuLayer(cfg, params, workspace_bytes=need)
+    main = torch.cuda.current_stream()
+    layer.forward(X, pm.FULL_RECOMPUTE, step=7)
+    layer.backward(dOUT)
+    torch.cuda.synchronize()
+    ref_dx = layer.dx.clone()
+    ref_grads = {k: v.clone() for k, v in layer.grads.items()}
+
+    side = torch.cuda.Stream()                      # default priority
+    src = torch.randn(cfg.tokens, cfg.hidden, device="cuda").to(layer.tdtype)
+    dst = torch.empty_like(src)
+    for rep in range(3):
+        layer.dx.zero_()
+        for v in layer.grads.values():
+            v.zero_()
+        B.lynx_layer_forward(layer.handle, layer.x, layer.out, pm.FULL_RECOMPUTE, 7, main)
+        fork = torch.cuda.Event()
+        fork.record(main)
+        side.wait_event(fork)
+        for seg in phases:
+            # one stand-in per communication window on the main stream, its segment beside it
+            B.lynx_comm_standin(dst, src, src.numel() * src.element_size(), 32, main)
+            B.lynx_recompute(layer.handle, seg, side)
+        join = torch.cuda.Event()
+        join.record(side)
+        main.wait_event(join)
+        B.lynx_layer_backward(layer.handle, layer.dout, layer.dx, layer.grads, main)
+        torch.cuda.synchronize()
+        assert torch.equal(dst, src)
+        assert torch.equal(layer.dx, ref_dx), rep
+        for k, v in layer.grads.items():
+            assert torch.equal(v, ref_grads[k]), (rep, k)
     layer.close()
 
 
