@@ -190,6 +190,11 @@ lynx_status lynx_layer_reset(lynx_layer_t layer);
  * sum of M_i over resident A_1..A_12, i.e. sum_i S_i*M_i right after forward.
  * peak bytes: high-water mark of the workspace since create. */
 lynx_status lynx_layer_live_mask(lynx_layer_t layer, uint32_t* live);
+/* The operators LYNX_SEG_ALL_MISSING stands for right now (bit i = OP_i): those
+ * whose outputs backward reads and that are not resident, plus, transitively,
+ * their absent inputs - what phase 5 would run (Sec. 4.2).  STATE when no
+ * forward is pending. */
+lynx_status lynx_layer_missing_mask(lynx_layer_t layer, uint32_t* missing);
 lynx_status lynx_layer_live_bytes(lynx_layer_t layer, size_t* bytes);
 lynx_status lynx_layer_peak_bytes(lynx_layer_t layer, size_t* bytes);
 

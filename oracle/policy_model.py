@@ -50,7 +50,9 @@ def activation_bytes(cfg) -> List[int]:
     p = cfg.local_heads * cfg.head_dim
     ss = cfg.micro_batch * cfg.local_heads * cfg.seq * cfg.seq
     th, stats = T * h * e, 2 * T * 4
-    return [th, th + stats, T * 3 * p * e, ss * e, ss * e, ss * e, T * p * e,
+    # C carries two fp32 attention row statistics per (batch element, head, row)
+    attn_stats = cfg.micro_batch * cfg.local_heads * cfg.seq * 2 * 4
+    return [th, th + stats, T * 3 * p * e, ss * e, ss * e, ss * e, T * p * e + attn_stats,
             th, th, th + stats, T * f * e, T * f * e, th, th]
 
 

@@ -91,6 +91,7 @@ _proto = {
                                       C.c_void_p]),
     "lynx_layer_reset": (C.c_int, [C.c_void_p]),
     "lynx_layer_live_mask": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
+    "lynx_layer_missing_mask": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
     "lynx_layer_live_bytes": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t)]),
     "lynx_layer_peak_bytes": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t)]),
     "lynx_layer_activation": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p),
@@ -215,6 +216,12 @@ def lynx_layer_reset(layer: int) -> None:
 def lynx_layer_live_mask(layer: int) -> int:
     v = C.c_uint32()
     _check(_lib.lynx_layer_live_mask(layer, C.byref(v)), "lynx_layer_live_mask")
+    return v.value
+
+
+def lynx_layer_missing_mask(layer: int) -> int:
+    v = C.c_uint32()
+    _check(_lib.lynx_layer_missing_mask(layer, C.byref(v)), "lynx_layer_missing_mask")
     return v.value
 
 

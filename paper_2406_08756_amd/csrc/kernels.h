@@ -73,6 +73,17 @@ hipError_t column_sum(int dtype, const void* x, void* dbias, float* scratch, int
 // product sum_j dP_ij P_ij of the softmax backward.
 hipError_t attn_rowdot(int dtype, const void* x, const void* y, float* out, int b, int a, int s, int d,
                        long long ld, hipStream_t st);
+// ---- attention without the seq x seq tensors (attn_fused.hip) ----------------------------
+// bf16 storage, head dimension 128, sequence a multiple of 128.
+bool attn_fused_supported(int dtype, int s, int d);
+size_t attn_fused_stats_bytes(int b, int a, int s);
+// Operators 3-6 in one launch: C [T, a * d] (row stride ldc) from QKV [T, 3 a d] (row stride
+// ld), bit-identical to S -> softmax -> dropout -> Pd V run one after the other; also leaves
+// per row (b, head, i) the maximum of the logits and the reciprocal of the row sum in
+// stats [b * a * s][2], from which the backward kernels rebuild P.
+hipError_t attn_fused_fwd(const void* qkv, long long ld, void* c, long long ldc, float* stats, AttnShape sh, int d,
+                          float scale, DropoutParams dp, hipStream_t st);
+
 // keep-mask bytes for parity checks: n elements starting at flat index 0 of
 // site 1/2, or the [b, a, s, s] tensor of site 0.
 hipError_t dropout_mask_hidden(uint8_t* out, size_t n, int site, DropoutParams dp, hipStream_t st);

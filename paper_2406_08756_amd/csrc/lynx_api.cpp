@@ -74,7 +74,9 @@ size_t act_bytes(const Dims& D, int i) {
     case 1: case 9: return th + stats;
     case 2: return static_cast<size_t>(D.T) * 3 * D.p * D.e;
     case 3: case 4: case 5: return D.ss * D.e;
-    case 6: return static_cast<size_t>(D.T) * D.p * D.e;
+    // C carries the attention row statistics (maximum, 1 / sum: two fp32 per row and head)
+    // that the kernels which never store S, P, Pd leave for their backward
+    case 6: return static_cast<size_t>(D.T) * D.p * D.e + static_cast<size_t>(D.b) * D.a * D.s * 2 * sizeof(float);
     case 10: case 11: return static_cast<size_t>(D.T) * D.f * D.e;
     default: return 0;
   }
@@ -87,6 +89,9 @@ struct Book {
   size_t off[kNumAct] = {};
   uint32_t retain = 0;
   int state = 0;  // 0 idle, 1 forward done / backward pending
+  // the policy keeps none of S, P, Pd and the shape is one the fused attention kernels take:
+  // operators 3-5 never run, operator 6 reads QKV alone
+  bool fused_attn = false;
 };
 
 }  // namespace
@@ -166,6 +171,9 @@ char* act_ptr(const Ctx& cx, int i) {
 float* stats_ptr(const Ctx& cx, int i) {  // mean[T], rstd[T] behind Y1 / Y2
   return reinterpret_cast<float*>(act_ptr(cx, i) + static_cast<size_t>(cx.L->D.T) * cx.L->D.h * cx.L->D.e);
 }
+float* attn_stats_ptr(const Ctx& cx) {  // (max, 1 / sum)[b a s] behind C
+  return reinterpret_cast<float*>(act_ptr(cx, 6) + static_cast<size_t>(cx.L->D.T) * cx.L->D.p * cx.L->D.e);
+}
 
 lynx_status alloc_act(Ctx& cx, int i) {
   if (i == 13) { cx.bk->live[13] = true; return LYNX_OK; }
@@ -200,7 +208,9 @@ char* temp_ptr(const Ctx& cx, const Temp& t) { return cx.L->base + t.off; }
 constexpr uint32_t kTappable = (1u << 12) | (1u << 10) | (1u << 9) | (1u << 8) | (1u << 7) | (1u << 6) |
                                (1u << 3) | (1u << 2) | (1u << 1);
 size_t tap_bytes(const Dims& D, int i) {
-  return (i == 1 || i == 9) ? static_cast<size_t>(D.T) * D.h * D.e : act_bytes(D, i);
+  if (i == 1 || i == 9) return static_cast<size_t>(D.T) * D.h * D.e;  // without the statistics
+  if (i == 6) return static_cast<size_t>(D.T) * D.p * D.e;
+  return act_bytes(D, i);
 }
 lynx_status tap(Ctx& cx, int i, const void* grad) {
   void* dst = cx.L->grad_tap[i];
@@ -425,14 +435,29 @@ lynx_status run_fused_linear(Ctx& cx, int lin) {
   return LYNX_OK;
 }
 
+// Operators 3-6 as one launch (attn_fused.hip): C and its row statistics from QKV.
+lynx_status run_fused_attention(Ctx& cx) {
+  lynx_layer_s* L = cx.L;
+  const Dims& D = L->D;
+  LYNX_TRY(alloc_act(cx, 6));
+  LYNX_LAUNCH(cx, 6, lynx::attn_fused_fwd(act_ptr(cx, 2), 3 * D.p, act_ptr(cx, 6), D.p, attn_stats_ptr(cx),
+                                          attn_shape(L), D.d, 1.0f / sqrtf(static_cast<float>(D.d)),
+                                          dropout_params(L), cx.st));
+  return LYNX_OK;
+}
+
 lynx_status forward_pass(Ctx& cx, uint32_t retain) {
   Book& bk = *cx.bk;
   bk.retain = (retain & 0x3FFFu) | kCallerOwned;
   bk.live[0] = true;
+  bk.fused_attn = !(bk.retain & 0x38u) && lynx::attn_fused_supported(cx.L->D.dtype, cx.L->D.s, cx.L->D.d);
   for (int i = 1; i <= kNumOps; ++i) {
     if (i == 5) continue;  // emitted by OP4's kernel
     int done = i;
-    if (i == 4) {
+    if (bk.fused_attn && (i == 3 || i == 4)) continue;
+    if (bk.fused_attn && i == 6) {
+      LYNX_TRY(run_fused_attention(cx));
+    } else if (i == 4) {
       LYNX_TRY(run_op(cx, 4, /*fuse_dropout=*/true, /*write_p=*/(bk.retain >> 4) & 1u));
       done = 5;  // OP4's launch covers OP5
     } else if ((i == 7 || i == 12) && can_fuse_linear(cx.L, i)) {
@@ -822,6 +847,13 @@ lynx_status lynx_layer_live_mask(lynx_layer_t L, uint32_t* live) {
   for (int i = 0; i < kNumAct; ++i)
     if (L->book.live[i]) m |= 1u << i;
   *live = m;
+  return LYNX_OK;
+}
+
+lynx_status lynx_layer_missing_mask(lynx_layer_t L, uint32_t* missing) {
+  if (L == nullptr || missing == nullptr) return LYNX_ERR_INVALID_ARG;
+  if (L->book.state != 1) return LYNX_ERR_STATE;
+  *missing = missing_closure(L->book);
   return LYNX_OK;
 }
 

@@ -5,6 +5,7 @@
 // dropout decisions are regenerated from the Philox counter, never read.
 // Written rows are zero-filled up to the next multiple of 128 columns so the
 // tensor-core attention products can read whole tiles of the diagonal blocks.
+#include "attn_math.h"
 #include "dropout_host.h"
 
 namespace lynx {
@@ -37,7 +38,7 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
       load8(S + row + j0, z[c]);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        z[c][k] = (j0 + k < nvalid) ? z[c][k] * scale : -INFINITY;
+        z[c][k] = (j0 + k < nvalid) ? softmax_logit(z[c][k], scale) : -INFINITY;
         m = fmaxf(m, z[c][k]);
       }
     } else {
@@ -46,23 +47,35 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
     }
   }
   m = wave_max(m);
-  float sum = 0.f;
+  // the row sum in its canonical order (attn_math.h): lane l of pass c holds vector l + 64 c,
+  // so an aligned block of 64 columns is 8 consecutive lanes
+  float a0 = 0.f, a1 = 0.f;
 #pragma unroll
-  for (int c = 0; c < NC; ++c)
+  for (int c = 0; c < NC; ++c) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      z[c][k] = __expf(z[c][k] - m);  // exp(-inf) = 0 for masked entries
-      sum += z[c][k];
+    for (int k = 0; k < 8; ++k) z[c][k] = softmax_exp(z[c][k], m);
+    float t0 = softmax_group4(z[c][0], z[c][1], z[c][2], z[c][3]);
+    float t1 = softmax_group4(z[c][4], z[c][5], z[c][6], z[c][7]);
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+      t0 += __shfl_xor(t0, o, kWave);
+      t1 += __shfl_xor(t1, o, kWave);
     }
-  sum = wave_sum(sum);
-  const float inv = 1.0f / sum;
+    const float blk = t0 + t1;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      a0 += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(blk), 16 * b));
+      a1 += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(blk), 16 * b + 8));
+    }
+  }
+  const float inv = softmax_inverse(a0 + a1);
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
     const int j0 = (lane + c * kWave) * 8;
     if (j0 < npad) {
       float pr[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) pr[k] = round_to_storage(z[c][k] * inv, P);
+      for (int k = 0; k < 8; ++k) pr[k] = softmax_prob<T>(z[c][k], inv);
       if (P != nullptr) store8(P + row + j0, pr);
       if (Pd != nullptr) {
         // entries beyond the diagonal are exactly 0 already; the zero padding needs no draw

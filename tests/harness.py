@@ -78,6 +78,8 @@ class GpuLayer:
         off = addr - self.workspace.data_ptr()
         e = 2 if cfg.dtype == synth.BF16 else 4
         n = cfg.tokens * cfg.hidden * e if act_id in (1, 9) else nbytes
+        if act_id == 6:
+            n = cfg.tokens * cfg.proj * e     # the attention row statistics follow
         return self.workspace[off:off + n].view(self.tdtype).clone()
 
     def activation(self, act_id) -> np.ndarray | None:
@@ -105,6 +107,8 @@ class GpuLayer:
             n = self.B.lynx_activation_bytes(cfg, act)
             if act in (1, 9):
                 n = cfg.tokens * cfg.hidden * e
+            if act == 6:
+                n = cfg.tokens * cfg.proj * e
             buf = torch.empty(n // e, dtype=self.tdtype, device="cuda")
             self.B.lynx_layer_set_gradient_tap(self.handle, act, buf)
             self.taps[name] = buf
