@@ -67,6 +67,11 @@ def slot_work(cfg):
         "b1_layernorm1_bwd": ("hbm", 4 * T * h * e),
         # dPd = dC V^T with the dropout + softmax backward in its store pass: reads P, writes dS
         "b6_rowdot": ("hbm", 2 * T * p * e), "b654_dscores": ("hbm", 2 * tri * e),
+        # attention without S, P, Pd (policies that keep none of them).  Forward: scores and
+        # context, the two products an unfused run performs (the kernel forms the scores three
+        # times; only the algorithmic two count).  Backward: dPd and dV likewise.
+        "op3456_attention_fused": ("mfma", 2 * att), "b654_dscores_fused": ("mfma", att),
+        "b6_dv_fused": ("mfma", att),
     }
 
 
@@ -92,8 +97,11 @@ def phase_flops(cfg, retain_mask):
     op_slot = {2: "op2_qkv_gemm", 3: "op3_scores", 6: "op6_context", 7: "op7_attn_proj_gemm",
                10: "op10_fc1_gemm", 12: "op12_fc2_gemm"}
     fwd = sum(w[n][1] for n in op_slot.values())
-    rec = sum(w[op_slot[i]][1] for i in regenerated_ops(cfg, retain_mask) if i in op_slot)
-    bwd = sum(v for n, (kind, v) in w.items() if n.startswith("b") and kind == "mfma")
+    ops = regenerated_ops(cfg, retain_mask)
+    if 6 in ops and 5 not in ops and not (retain_mask >> 5) & 1:
+        ops = ops + [3]    # operator 6 ran fused with operators 3-5: the score product is part of what it regenerates
+    rec = sum(w[op_slot[i]][1] for i in ops if i in op_slot)
+    bwd = sum(v for n, (kind, v) in w.items() if n.startswith("b") and kind == "mfma" and not n.endswith("_fused"))
     return fwd, rec, bwd
 
 
@@ -323,6 +331,8 @@ def main():
     ap.add_argument("--zeros", action="store_true",
                     help="diagnostic: all-zero inputs and parameters (shows how far the dense products are "
                          "held back by power rather than by their schedule); the line says data=zeros")
+    ap.add_argument("--fused-attention", action="store_true",
+                    help="set LYNX_FLAG_FUSED_ATTENTION: no seq x seq activation under policies that drop S, P, Pd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (the known-size kernel that "
@@ -342,6 +352,8 @@ def main():
     if args.slice:
         return slice_bench(args)
     cfg = synth.CONFIGS[args.config]
+    if args.fused_attention:
+        cfg = cfg.with_(flags=1)
     policy = args.policy or {"C3": "elementwise_only", "C2": "full"}.get(args.config, "full")
     mask = POLICIES[policy]
     if args.retain_mask is not None:
@@ -527,13 +539,14 @@ def main():
         "data": "zeros (diagnostic, not a benchmark figure)" if args.zeros else "synthetic",
         "config": {"workload": "%s: h=%d a=%d d=%d f=%d s=%d b=%d tp=%d, policy=%s" % (
             args.config, cfg.hidden, cfg.local_heads, cfg.head_dim, cfg.local_ffn, cfg.seq,
-            cfg.micro_batch, cfg.tp_size, policy),
+            cfg.micro_batch, cfg.tp_size, policy + (", fused attention" if cfg.flags & 1 else "")),
             "timed_region": "lynx_recompute(all missing) + lynx_layer_backward per step, HIP events; "
                             "each step also runs lynx_layer_forward first (forward_ms, inside wall_ms_per_step)"},
         "recompute_ms": round(rec_ms, 4), "backward_ms": round(bwd_ms, 4), "forward_ms": round(fwd_ms, 4),
         "wall_ms_per_step": round(wall_ms, 4),
         "median_ms_per_step": round(median_ms, 4), "min_ms_per_step": round(min_ms, 4),
         "algorithmic_tflop": {"forward": fwd_f / 1e12, "recompute": rec_f / 1e12, "backward": bwd_f / 1e12},
+        "workspace_bytes": ws_bytes,
         "roofline": roofline,
         "kernels": kernels,
     }

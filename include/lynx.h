@@ -75,8 +75,22 @@ typedef struct {
   float ln_eps;
   uint64_t seed;       /* Philox key */
   uint32_t layer_id;   /* enters the Philox counter */
-  uint32_t reserved;   /* must be 0 */
+  uint32_t flags;      /* LYNX_FLAG_*; other bits must be 0 */
 } lynx_layer_config;
+
+/* Attention without the seq x seq tensors.  Under a retain mask that keeps none of S, P
+ * and Pd (the tensors Selective Recomputation drops, Sec. 2.2) and for shapes the kernels
+ * take (bf16, head_dim 128, seq a multiple of 128), operators 3-5 never run: operator 6
+ * forms C from QKV in one launch and leaves two fp32 row statistics per (batch element,
+ * head, row) behind C; backward rebuilds P and Pd from them tile by tile.  Then naming
+ * operators 3-5 in a segment is a no-op, operator 6 depends on QKV alone, backward reads
+ * QKV and C instead of P and Pd, and no seq x seq activation is ever allocated (one
+ * seq x seq gradient, dS, remains as a transient of backward).  Every result is
+ * bit-identical to the unfused kernels'.  It trades arithmetic for memory: the dropout
+ * generator and the exponentials run once more per kernel that needs P, which on this chip
+ * costs more time than the seq x seq traffic it saves; the peak workspace of a
+ * full-recompute layer drops by about three seq x seq tensors.  Off by default. */
+#define LYNX_FLAG_FUSED_ATTENTION 1u
 
 /* Device pointers to the parameters, borrowed until the next set_params or
  * destroy.  Shapes: wqkv [3*a*d, h], bqkv [3*a*d], wo [h, a*d], bo [h],
@@ -105,7 +119,8 @@ typedef struct {
 
 /* M_i of the paper's memory constraint (Eq. 8): bytes of activation act_id
  * (0..13) for this shape.  LayerNorm outputs (A1, A9) include their two fp32
- * per-token statistics.  Returns 0 for a bad argument. */
+ * per-token statistics, the context A6 two fp32 attention row statistics per
+ * (batch element, head, row).  Returns 0 for a bad argument. */
 size_t lynx_activation_bytes(const lynx_layer_config* cfg, int act_id);
 
 /* Workspace (device bytes) that lynx_layer_create needs so that

@@ -43,6 +43,7 @@ class LayerConfig:
     ln_eps: float = 1e-5
     seed: int = 0         # dropout generator key
     layer_id: int = 0
+    flags: int = 0        # 1: attention without the seq x seq tensors where the policy allows
 
     @property
     def tokens(self) -> int:

@@ -56,18 +56,37 @@ def activation_bytes(cfg) -> List[int]:
             th, th, th + stats, T * f * e, T * f * e, th, th]
 
 
-def missing_closure(live: Set[int]) -> List[int]:
+def fused_attention(cfg, retain_mask: int) -> bool:
+    """Whether the layer runs its attention without the seq x seq tensors: the
+    configuration asks for it (flags bit 0), the policy keeps none of S, P, Pd (the tensors Selective Recomputation singles
+    out, Sec. 2.2) and the shape is one those kernels are built for (bf16,
+    head dimension 128, sequence a multiple of 128).  Then operators 3-5 never
+    run, operator 6 reads QKV alone, and backward reads C (with its row
+    statistics) instead of P and Pd."""
+    return (bool(getattr(cfg, "flags", 0) & 1) and not (retain_mask & 0x38) and cfg.dtype == 1
+            and cfg.head_dim == 128 and cfg.seq % 128 == 0 and cfg.seq >= 128)
+
+
+def parents_of(i: int, fused: bool) -> tuple:
+    return (2,) if (fused and i == 6) else PARENTS[i]
+
+
+def backward_needs(fused: bool) -> tuple:
+    return tuple(i for i in BACKWARD_NEEDS if not (fused and i in (4, 5)))
+
+
+def missing_closure(live: Set[int], fused: bool = False) -> List[int]:
     """Operators that must run, in index order, so that backward finds every
     activation it reads: the needed-but-absent ones plus, transitively, their
     absent parents."""
     todo: Set[int] = set()
-    stack = [i for i in BACKWARD_NEEDS if i not in live]
+    stack = [i for i in backward_needs(fused) if i not in live]
     while stack:
         i = stack.pop()
         if i in todo:
             continue
         todo.add(i)
-        stack.extend(j for j in PARENTS[i] if j not in live and j not in todo)
+        stack.extend(j for j in parents_of(i, fused) if j not in live and j not in todo)
     return sorted(todo)
 
 
@@ -75,10 +94,12 @@ class LayerBookkeeping:
     """Which activations are resident, call by call."""
 
     def __init__(self, cfg):
+        self.cfg = cfg
         self.M = activation_bytes(cfg)
         self.live: Set[int] = set()
         self.retain: Set[int] = set()
         self.state = "idle"
+        self.fused = False
 
     def forward(self, retain_mask: int):
         if self.state != "idle":
@@ -86,6 +107,7 @@ class LayerBookkeeping:
         self.retain = {i for i in range(1, 13) if (retain_mask >> i) & 1} | {0, 13}
         self.live = set(self.retain)
         self.state = "forwarded"
+        self.fused = fused_attention(self.cfg, retain_mask)
 
     def _release_stepping_stones(self):
         # a regenerated activation that backward never reads and whose
@@ -101,15 +123,17 @@ class LayerBookkeeping:
         if self.state != "forwarded":
             raise StateError("recompute before forward")
         if segment_mask == SEG_ALL_MISSING:
-            ops = missing_closure(self.live)
+            ops = missing_closure(self.live, self.fused)
         else:
             ops = [i for i in range(1, N_OPS + 1) if (segment_mask >> i) & 1]
+        if self.fused:
+            ops = [i for i in ops if i not in (3, 4, 5)]   # those operators do not exist in this mode
         # validate before changing anything
         live = set(self.live)
         for i in ops:
             if i in live:
                 continue
-            for j in PARENTS[i]:
+            for j in parents_of(i, self.fused):
                 if j not in live:
                     raise DependencyError(f"OP{i} needs A{j}")
             live.add(i)

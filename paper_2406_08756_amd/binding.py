@@ -31,6 +31,7 @@ LYNX_SEG_ALL_MISSING = 0xFFFFFFFF
 LYNX_NUM_ACTIVATIONS = 14
 LYNX_PROFILE_SLOTS = 40
 LYNX_STATIC_WORKSPACE_BYTES = 64 << 20
+LYNX_FLAG_FUSED_ATTENTION = 1
 PARAM_FIELDS = ("wqkv", "bqkv", "wo", "bo", "w1", "b1", "w2", "b2", "g1", "be1", "g2", "be2")
 
 
@@ -39,7 +40,7 @@ class lynx_layer_config(C.Structure):
                 ("head_dim", C.c_int32), ("local_ffn", C.c_int32), ("seq", C.c_int32),
                 ("micro_batch", C.c_int32), ("tp_size", C.c_int32), ("tp_rank", C.c_int32),
                 ("causal", C.c_int32), ("dropout_p", C.c_float), ("ln_eps", C.c_float),
-                ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("reserved", C.c_uint32)]
+                ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("flags", C.c_uint32)]
 
 
 class lynx_params(C.Structure):
@@ -144,7 +145,7 @@ def make_config(cfg) -> lynx_layer_config:
     return lynx_layer_config(int(cfg.dtype), cfg.hidden, cfg.local_heads, cfg.head_dim,
                              cfg.local_ffn, cfg.seq, cfg.micro_batch, cfg.tp_size, cfg.tp_rank,
                              int(cfg.causal), float(cfg.dropout_p), float(cfg.ln_eps),
-                             int(cfg.seed), int(cfg.layer_id), 0)
+                             int(cfg.seed), int(cfg.layer_id), int(getattr(cfg, "flags", 0)))
 
 
 def lynx_status_string(status: int) -> str:

@@ -404,7 +404,185 @@ __global__ void __launch_bounds__(kThreads) attn_fwd_fused_kernel(AttnFusedArgs 
     *reinterpret_cast<uintx4_t*>(cw + static_cast<long long>(8 * u + lr) * g.ldc + lc * 8) = rows[u];
 }
 
+// ---------------------------------------------------------------------------
+// Backward, first kernel: dS of one block of 128 query rows (B6 + B5 + B4).  Per tile the
+// scores are formed again and turned into P with the stored row statistics, dPd = dC V^T is
+// formed next to them, and dS = scale P (keep c dPd - dot) leaves for HBM: the one seq x seq
+// tensor of the fused path, a transient that the dQ and dK products consume.
+// LDS: Q | dC (resident) | K | V (streamed; after the two products they are the staging areas
+// of S and dPd, and the next tiles arrive during the elementwise phase).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) attn_bwd_ds_kernel(AttnFusedArgs g, bf16_t* __restrict__ dS) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* sQ = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sdC = sQ + kOpElems;
+  bf16_t* sK = sdC + kOpElems;
+  bf16_t* sV = sK + kOpElems;
+
+  const int tiles = g.s / kTile;
+  const int t = blockIdx.x / g.nz;
+  const int bz = blockIdx.x - t * g.nz;
+  const int tm = tiles - 1 - t;
+  const int bi = bz / g.a, hd = bz - bi * g.a;
+  const long long tok0 = static_cast<long long>(bi) * g.s;
+  const bf16_t* Qb = g.qkv + (tok0 + tm * kTile) * g.ld + hd * kD;
+  const bf16_t* Kb = g.qkv + tok0 * g.ld + g.p + hd * kD;
+  const bf16_t* Vb = Kb + g.p;
+  const bf16_t* dCb = g.dc + (tok0 + tm * kTile) * g.lddc + hd * kD;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+  const int lr = lane >> 3, lc = lane & 7;
+
+  // this lane's eight rows: statistics, dot products, dropout indices
+  float rm[8], rinv[8], dot[8];
+  uint64_t gidx[8];
+  const uint64_t rows_before = (static_cast<uint64_t>(bi) * g.global_heads + g.head0 + hd) * g.s;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const long long i = tm * kTile + wm0 + 8 * u + lr;
+    const float2 st = *reinterpret_cast<const float2*>(g.stats + (static_cast<long long>(bz) * g.s + i) * 2);
+    rm[u] = st.x;
+    rinv[u] = st.y;
+    dot[u] = g.rowdot[static_cast<long long>(bz) * g.s + i];
+    gidx[u] = (rows_before + i) * static_cast<uint64_t>(g.s) + wn0 + lc * 8;
+  }
+#pragma unroll
+  for (int u = 0; u < 8; ++u) asm volatile("" : "+v"(rm[u]), "+v"(rinv[u]), "+v"(dot[u]));
+
+  load_tile<SLK>(Qb, g.ld, sQ, wave, lane);
+  load_tile<SLK>(dCb, g.lddc, sdC, wave, lane);
+  load_tile<SLK>(Kb, g.ld, sK, wave, lane);
+  load_tile<SLK>(Vb, g.ld, sV, wave, lane);
+
+  bf16_t* stageS = sK + wave * (64 * 64);
+  bf16_t* stageD = sV + wave * (64 * 64);
+  bf16_t* out = dS + (static_cast<long long>(bz) * g.s + tm * kTile + wm0) * g.s + wn0;
+  for (int tn = 0; tn <= tm; ++tn) {
+    // K(tn), V(tn) have landed; issued after them: the previous tile's eight stores
+    if (tn == 0) wait_vmcnt<0>();
+    else wait_vmcnt<8>();
+    block_barrier();
+    floatx16_t accS[2][2], accD[2][2];
+    clear(accS);
+    clear(accD);
+    product_kmajor(sQ, sK, wm0, wn0, lane, accS);
+    product_kmajor(sdC, sV, wm0, wn0, lane, accD);
+    block_barrier();  // every wavefront has read K(tn) and V(tn): their buffers become staging areas
+    uintx4_t rowsS[8], rowsD[8];
+    quadrant_to_rows(accS, stageS, lane, rowsS);
+    quadrant_to_rows(accD, stageD, lane, rowsD);
+    block_barrier();  // every wavefront has its rows: the buffers can take the next tiles
+    if (tn < tm) {
+      load_tile<SLK>(Kb + static_cast<long long>(tn + 1) * kTile * g.ld, g.ld, sK, wave, lane);
+      load_tile<SLK>(Vb + static_cast<long long>(tn + 1) * kTile * g.ld, g.ld, sV, wave, lane);
+    }
+    const bool diag = tn == tm;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int row = wm0 + 8 * u + lr, col0 = wn0 + lc * 8;
+      float p[8], dp[8], ds[8];
+      probabilities8(rowsS[u], g.scale, rm[u], rinv[u], col0, diag ? row + 1 : kTile, p);
+      unpack8(rowsD[u], dp);
+      dropout_apply8(g.key, (gidx[u] + static_cast<uint64_t>(tn) * kTile) >> 3, dp);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ds[k] = softmax_bwd(p[k], dp[k], dot[u], g.scale);
+      store8(out + static_cast<long long>(8 * u + lr) * g.s + tn * kTile + lc * 8, ds);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Backward, second kernel: dV of one block of 128 key rows (the other half of B6).  Walks the
+// query blocks i >= j: the scores of the tile are formed again, turned into P and Pd, and
+// Pd^T dC is accumulated in ascending i.
+// LDS: K (resident) | Q (two buffers: the next block is requested a tile ahead; after the
+// score product the current one is the staging area and then holds Pd as an operand tile) |
+// dC with the token index as the contraction row.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads) attn_bwd_dv_kernel(AttnFusedArgs g) {
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* sK = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sQ = sK + kOpElems;  // two buffers
+  bf16_t* sdC = sQ + 2 * kOpElems;
+
+  const int tiles = g.s / kTile;
+  const int t = blockIdx.x / g.nz;
+  const int bz = blockIdx.x - t * g.nz;
+  const int tj = t;  // key block; the longest walks (small j) first
+  const int bi = bz / g.a, hd = bz - bi * g.a;
+  const long long tok0 = static_cast<long long>(bi) * g.s;
+  const bf16_t* Qb = g.qkv + tok0 * g.ld + hd * kD;
+  const bf16_t* Kb = g.qkv + (tok0 + tj * kTile) * g.ld + g.p + hd * kD;
+  const bf16_t* dCb = g.dc + tok0 * g.lddc + hd * kD;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+  const int lr = lane >> 3, lc = lane & 7;
+  const uint64_t rows_before = (static_cast<uint64_t>(bi) * g.global_heads + g.head0 + hd) * g.s;
+
+  load_tile<SLK>(Kb, g.ld, sK, wave, lane);
+  load_tile<SLK>(Qb + static_cast<long long>(tj) * kTile * g.ld, g.ld, sQ, wave, lane);
+  load_tile<SLM>(dCb + static_cast<long long>(tj) * kTile * g.lddc, g.lddc, sdC, wave, lane);
+
+  floatx16_t accV[2][2];
+  clear(accV);
+  for (int ti = tj; ti < tiles; ++ti) {
+    bf16_t* sQc = sQ + ((ti - tj) & 1) * kOpElems;
+    // the statistics of this query block's rows (this lane's eight rows of the store layout)
+    float rm[8], rinv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const long long i = ti * kTile + wm0 + 8 * u + lr;
+      const float2 st = *reinterpret_cast<const float2*>(g.stats + (static_cast<long long>(bz) * g.s + i) * 2);
+      rm[u] = st.x;
+      rinv[u] = st.y;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) asm volatile("" : "+v"(rm[u]), "+v"(rinv[u]));
+    wait_vmcnt<0>();   // Q(ti), dC(ti) (and, the first time, K) have landed
+    block_barrier();   // also: every wavefront is done with the previous Pd operand tile
+    if (ti + 1 < tiles)
+      load_tile<SLK>(Qb + static_cast<long long>(ti + 1) * kTile * g.ld, g.ld, sQ + ((ti + 1 - tj) & 1) * kOpElems, wave, lane);
+    floatx16_t acc[2][2];
+    clear(acc);
+    product_kmajor(sQc, sK, wm0, wn0, lane, acc);
+    block_barrier();   // every wavefront has read Q(ti): its buffer becomes the staging area
+    uintx4_t rows[8];
+    quadrant_to_rows(acc, sQc + wave * (64 * 64), lane, rows);
+    block_barrier();   // every wavefront has its rows: the buffer can take the Pd operand tile
+    const bool diag = ti == tj;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int row = wm0 + 8 * u + lr, col0 = wn0 + lc * 8;
+      float p[8];
+      probabilities8(rows[u], g.scale, rm[u], rinv[u], col0, diag ? row + 1 : kTile, p);
+      const uint64_t gi = (rows_before + ti * kTile + row) * static_cast<uint64_t>(g.s) + tj * kTile + col0;
+      dropout_apply8(g.key, gi >> 3, p);
+      rows_to_operand_mn(sQc, row, col0, p);
+    }
+    wait_lgkmcnt0();
+    block_barrier();
+    product_tn(sQc, sdC, wm0, wn0, lane, accV);
+    if (ti + 1 < tiles) {
+      block_barrier();  // every wavefront is done with dC(ti)
+      load_tile<SLM>(dCb + static_cast<long long>(ti + 1) * kTile * g.lddc, g.lddc, sdC, wave, lane);
+    }
+  }
+  // dV: round, through the staging area, whole rows out
+  block_barrier();
+  uintx4_t rows[8];
+  quadrant_to_rows(accV, sK + wave * (64 * 64), lane, rows);
+  bf16_t* vw = g.dqkv + (tok0 + tj * kTile + wm0) * g.lddq + 2 * g.p + hd * kD + wn0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+    *reinterpret_cast<uintx4_t*>(vw + static_cast<long long>(8 * u + lr) * g.lddq + lc * 8) = rows[u];
+}
+
 constexpr size_t kFwdLds = 4 * static_cast<size_t>(kOpElems) * sizeof(bf16_t) + 4 * kTile * sizeof(float);
+constexpr size_t kBwdLds = 4 * static_cast<size_t>(kOpElems) * sizeof(bf16_t);
 
 #define LYNX_RAISE_LDS(kern, bytes)                                                              \
   do {                                                                                           \
@@ -433,6 +611,42 @@ hipError_t attn_fused_fwd(const void* qkv, long long ld, void* c, long long ldc,
   g.key = make_dropout_key(dp, 0); g.global_heads = sh.global_heads; g.head0 = sh.head0;
   LYNX_RAISE_LDS(attn_fwd_fused_kernel, kFwdLds);
   hipLaunchKernelGGL(attn_fwd_fused_kernel, dim3((sh.s / kTile) * g.nz), dim3(kThreads), kFwdLds, st, g);
+  return hipGetLastError();
+}
+
+
+namespace {
+AttnFusedArgs bwd_args(const void* qkv, long long ld, const void* dc, long long lddc, const float* stats, AttnShape sh,
+                       int d, float scale, DropoutParams dp) {
+  AttnFusedArgs g{};
+  g.qkv = static_cast<const bf16_t*>(qkv); g.ld = ld; g.p = sh.a * d;
+  g.stats = const_cast<float*>(stats); g.dc = static_cast<const bf16_t*>(dc); g.lddc = lddc;
+  g.s = sh.s; g.a = sh.a; g.nz = sh.b * sh.a; g.scale = scale;
+  g.key = make_dropout_key(dp, 0); g.global_heads = sh.global_heads; g.head0 = sh.head0;
+  return g;
+}
+}  // namespace
+
+hipError_t attn_fused_bwd_ds(const void* qkv, long long ld, const void* dc, long long lddc, const float* stats,
+                             const float* rowdot, void* ds, AttnShape sh, int d, float scale, DropoutParams dp,
+                             hipStream_t st) {
+  if (!attn_fused_supported(1, sh.s, d) || ld % 8 || lddc % 8) return hipErrorInvalidValue;
+  AttnFusedArgs g = bwd_args(qkv, ld, dc, lddc, stats, sh, d, scale, dp);
+  g.rowdot = rowdot;
+  LYNX_RAISE_LDS(attn_bwd_ds_kernel, kBwdLds);
+  hipLaunchKernelGGL(attn_bwd_ds_kernel, dim3((sh.s / kTile) * g.nz), dim3(kThreads), kBwdLds, st, g,
+                     static_cast<bf16_t*>(ds));
+  return hipGetLastError();
+}
+
+hipError_t attn_fused_bwd_dv(const void* qkv, long long ld, const void* dc, long long lddc, const float* stats,
+                             void* dqkv, long long lddq, AttnShape sh, int d, float scale, DropoutParams dp,
+                             hipStream_t st) {
+  if (!attn_fused_supported(1, sh.s, d) || ld % 8 || lddc % 8 || lddq % 8) return hipErrorInvalidValue;
+  AttnFusedArgs g = bwd_args(qkv, ld, dc, lddc, stats, sh, d, scale, dp);
+  g.dqkv = static_cast<bf16_t*>(dqkv); g.lddq = lddq;
+  LYNX_RAISE_LDS(attn_bwd_dv_kernel, kBwdLds);
+  hipLaunchKernelGGL(attn_bwd_dv_kernel, dim3((sh.s / kTile) * g.nz), dim3(kThreads), kBwdLds, st, g);
   return hipGetLastError();
 }
 

@@ -92,6 +92,19 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
   return v;
 }
+// Sum over each aligned group of 8 lanes in the tree order ((v0 + v1) + (v2 + v3)) + ((v4 + v5)
+// + (v6 + v7)); every lane of the group gets the same bits (addition commutes).  Data-parallel
+// lane permutes inside the vector ALU: no trip through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float lane_permute(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float group8_sum(float v) {
+  v += lane_permute<0xB1>(v);   // quad_perm [1, 0, 3, 2]: lane ^ 1
+  v += lane_permute<0x4E>(v);   // quad_perm [2, 3, 0, 1]: lane ^ 2
+  v += lane_permute<0x141>(v);  // row_half_mirror: lane 7 - i, a lane of the other quad (all four hold its sum)
+  return v;
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));

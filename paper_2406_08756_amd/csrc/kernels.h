@@ -84,6 +84,17 @@ size_t attn_fused_stats_bytes(int b, int a, int s);
 hipError_t attn_fused_fwd(const void* qkv, long long ld, void* c, long long ldc, float* stats, AttnShape sh, int d,
                           float scale, DropoutParams dp, hipStream_t st);
 
+// Backward of operators 6-4 without P and Pd.  First kernel: dS [b, a, s, s] (dense layout,
+// j <= i defined) = scale P (keep c round(dC V^T) - rowdot), P rebuilt from QKV and stats.
+// Second kernel: the v block of dqkv [T, 3 a d] = Pd^T dC, Pd rebuilt likewise.  Both
+// bit-identical to the unfused kernels run on stored P and Pd.
+hipError_t attn_fused_bwd_ds(const void* qkv, long long ld, const void* dc, long long lddc, const float* stats,
+                             const float* rowdot, void* ds, AttnShape sh, int d, float scale, DropoutParams dp,
+                             hipStream_t st);
+hipError_t attn_fused_bwd_dv(const void* qkv, long long ld, const void* dc, long long lddc, const float* stats,
+                             void* dqkv, long long lddq, AttnShape sh, int d, float scale, DropoutParams dp,
+                             hipStream_t st);
+
 // keep-mask bytes for parity checks: n elements starting at flat index 0 of
 // site 1/2, or the [b, a, s, s] tensor of site 0.
 hipError_t dropout_mask_hidden(uint8_t* out, size_t n, int site, DropoutParams dp, hipStream_t st);

@@ -54,7 +54,7 @@ bool make_dims(const lynx_layer_config* c, Dims* o) {
   if (!(c->dropout_p >= 0.0f && c->dropout_p < 1.0f)) return false;
   if (!(c->ln_eps >= 0.0f)) return false;
   if (c->tp_size <= 0 || c->tp_rank < 0 || c->tp_rank >= c->tp_size) return false;
-  if (c->layer_id >= (1u << 30) || c->causal != 1 || c->reserved != 0) return false;
+  if (c->layer_id >= (1u << 30) || c->causal != 1 || (c->flags & ~LYNX_FLAG_FUSED_ATTENTION)) return false;
   const long long T = static_cast<long long>(c->micro_batch) * c->seq;
   if (T > (1ll << 24)) return false;
   o->dtype = c->dtype;
@@ -151,7 +151,8 @@ struct Ctx {  // one pass (rehearsal or real) of a call
 // profile slots: 1..13 = forward operators; then the backward kernels in order
 enum BackwardSlot {
   kB13Dropout = 14, kB12Grads, kB11Gelu, kB10Grads, kB98LayerNormDropout, kB7Grads, kB6DPd,
-  kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kB6RowDot, kB654DScores, kNumSlots
+  kB6DV, kB54Softmax, kB3DQ, kB3DK, kB2Grads, kB2BiasGrad, kB1LayerNorm, kB6RowDot, kB654DScores,
+  kOp36Fused, kB654DScoresFused, kB6DVFused, kNumSlots
 };
 static_assert(kNumSlots <= LYNX_PROFILE_SLOTS, "profile slots");
 static_assert(LYNX_STATIC_WORKSPACE_BYTES == lynx::kStaticWorkspaceBytes, "header and library agree on the block size");
@@ -161,7 +162,8 @@ const char* const kSlotNames[kNumSlots] = {
     "op11_gelu", "op12_fc2_gemm", "op13_bias_dropout_add2", "b13_dropout_bwd",
     "b12_fc2_dgrad_wgrad", "b11_gelu_bwd", "b10_fc1_dgrad_wgrad",
     "b98_layernorm2_dropout_bwd", "b7_proj_dgrad_wgrad", "b6_dpd", "b6_dv", "b54_softmax_dropout_bwd", "b3_dq",
-    "b3_dk", "b2_qkv_dgrad_wgrad", "b2_bias_grad", "b1_layernorm1_bwd", "b6_rowdot", "b654_dscores"};
+    "b3_dk", "b2_qkv_dgrad_wgrad", "b2_bias_grad", "b1_layernorm1_bwd", "b6_rowdot", "b654_dscores",
+    "op3456_attention_fused", "b654_dscores_fused", "b6_dv_fused"};
 
 char* act_ptr(const Ctx& cx, int i) {
   if (i == 0) return const_cast<char*>(static_cast<const char*>(cx.L->x));
@@ -440,7 +442,7 @@ lynx_status run_fused_attention(Ctx& cx) {
   lynx_layer_s* L = cx.L;
   const Dims& D = L->D;
   LYNX_TRY(alloc_act(cx, 6));
-  LYNX_LAUNCH(cx, 6, lynx::attn_fused_fwd(act_ptr(cx, 2), 3 * D.p, act_ptr(cx, 6), D.p, attn_stats_ptr(cx),
+  LYNX_LAUNCH(cx, kOp36Fused, lynx::attn_fused_fwd(act_ptr(cx, 2), 3 * D.p, act_ptr(cx, 6), D.p, attn_stats_ptr(cx),
                                           attn_shape(L), D.d, 1.0f / sqrtf(static_cast<float>(D.d)),
                                           dropout_params(L), cx.st));
   return LYNX_OK;
@@ -450,7 +452,8 @@ lynx_status forward_pass(Ctx& cx, uint32_t retain) {
   Book& bk = *cx.bk;
   bk.retain = (retain & 0x3FFFu) | kCallerOwned;
   bk.live[0] = true;
-  bk.fused_attn = !(bk.retain & 0x38u) && lynx::attn_fused_supported(cx.L->D.dtype, cx.L->D.s, cx.L->D.d);
+  bk.fused_attn = (cx.L->cfg.flags & LYNX_FLAG_FUSED_ATTENTION) && !(bk.retain & 0x38u) &&
+                  lynx::attn_fused_supported(cx.L->D.dtype, cx.L->D.s, cx.L->D.d);
   for (int i = 1; i <= kNumOps; ++i) {
     if (i == 5) continue;  // emitted by OP4's kernel
     int done = i;
@@ -488,18 +491,30 @@ void release_stepping_stones(Ctx& cx) {
   }
 }
 
+// The operator graph as this call sees it.  With the attention fused (Book::fused_attn)
+// operators 3-5 do not exist: operator 6 reads QKV alone and backward reads C with its row
+// statistics instead of P and Pd.
+int parent_of(const Book& bk, int op, int k) {
+  if (bk.fused_attn && op == 6) return k == 0 ? 2 : -1;
+  return k < 3 ? kParents[op][k] : -1;
+}
+uint32_t backward_needs(const Book& bk) {
+  return bk.fused_attn ? (kBackwardNeeds & ~((1u << 4) | (1u << 5))) : kBackwardNeeds;
+}
+
 uint32_t missing_closure(const Book& bk) {
   uint32_t todo = 0;
   std::vector<int> stack;
+  const uint32_t needs = backward_needs(bk);
   for (int i = 0; i < kNumAct; ++i)
-    if (((kBackwardNeeds >> i) & 1u) && !bk.live[i]) stack.push_back(i);
+    if (((needs >> i) & 1u) && !bk.live[i]) stack.push_back(i);
   while (!stack.empty()) {
     const int i = stack.back();
     stack.pop_back();
     if ((todo >> i) & 1u) continue;
     todo |= 1u << i;
-    for (int k = 0; k < 3 && kParents[i][k] >= 0; ++k) {
-      const int j = kParents[i][k];
+    for (int k = 0; k < 3 && parent_of(bk, i, k) >= 0; ++k) {
+      const int j = parent_of(bk, i, k);
       if (!bk.live[j] && !((todo >> j) & 1u)) stack.push_back(j);
     }
   }
@@ -510,20 +525,23 @@ lynx_status recompute_pass(Ctx& cx, uint32_t segment) {
   Book& bk = *cx.bk;
   if (segment == LYNX_SEG_ALL_MISSING) segment = missing_closure(bk);
   if (segment & ~0x3FFFu) return LYNX_ERR_INVALID_ARG;
+  if (bk.fused_attn) segment &= ~0x38u;  // operators 3-5 do not exist in this mode: naming them is a no-op
   // dependency rule: every input stored or produced earlier in the segment
   {
     bool have[kNumAct];
     for (int i = 0; i < kNumAct; ++i) have[i] = bk.live[i];
     for (int i = 1; i <= kNumOps; ++i) {
       if (!((segment >> i) & 1u) || have[i]) continue;
-      for (int k = 0; k < 3 && kParents[i][k] >= 0; ++k)
-        if (!have[kParents[i][k]]) return LYNX_ERR_DEPENDENCY;
+      for (int k = 0; k < 3 && parent_of(bk, i, k) >= 0; ++k)
+        if (!have[parent_of(bk, i, k)]) return LYNX_ERR_DEPENDENCY;
       have[i] = true;
     }
   }
   for (int i = 1; i <= kNumOps; ++i) {
     if (!((segment >> i) & 1u) || bk.live[i]) continue;
-    if (i == 4 && ((segment >> 5) & 1u) && !bk.live[5]) {
+    if (bk.fused_attn && i == 6) {
+      LYNX_TRY(run_fused_attention(cx));
+    } else if (i == 4 && ((segment >> 5) & 1u) && !bk.live[5]) {
       LYNX_TRY(run_op(cx, 4, /*fuse_dropout=*/true));
     } else if ((i == 7 || i == 12) && ((segment >> (i + 1)) & 1u) && !bk.live[i + 1] &&
                can_fuse_linear(cx.L, i)) {
@@ -649,7 +667,15 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
   dpd.epi.global_heads = D.a * L->cfg.tp_size;
   dpd.epi.head0 = L->cfg.tp_rank * D.a;
   const bool fused_ds = lynx::gemm_mfma_supported(dt, dpd);
-  if (fused_ds) {
+  if (cx.bk->fused_attn) {
+    // neither P nor Pd exists: both kernels rebuild them from QKV and the row statistics of C
+    float* rowdot = reinterpret_cast<float*>(temp_ptr(cx, t_rowdot));
+    LYNX_LAUNCH(cx, kB6RowDot, lynx::attn_rowdot(dt, temp_ptr(cx, t_dc), act_ptr(cx, 6), rowdot, D.b, D.a, D.s, D.d,
+                                                 D.p, cx.st));
+    LYNX_LAUNCH(cx, kB654DScoresFused, lynx::attn_fused_bwd_ds(qkv, 3 * D.p, temp_ptr(cx, t_dc), D.p, attn_stats_ptr(cx),
+                                                          rowdot, temp_ptr(cx, t_dpd), attn_shape(L), D.d,
+                                                          dpd.epi.scale, dropout_params(L), cx.st));
+  } else if (fused_ds) {
     LYNX_LAUNCH(cx, kB6RowDot, lynx::attn_rowdot(dt, temp_ptr(cx, t_dc), act_ptr(cx, 6),
                                                  reinterpret_cast<float*>(temp_ptr(cx, t_rowdot)), D.b, D.a, D.s,
                                                  D.d, D.p, cx.st));
@@ -659,13 +685,19 @@ lynx_status backward_pass(Ctx& cx, const void* d_out, void* d_x, const lynx_grad
     LYNX_LAUNCH(cx, kB6DPd, lynx::gemm(dt, dpd, cx.st));
   }
   free_temp(cx, &t_rowdot);
-  LYNX_LAUNCH(cx, kB6DV, lynx::gemm(dt, attn_cols(act_ptr(cx, 5), temp_ptr(cx, t_dc), D.p,
-                                           const_cast<char*>(col_block(dqkv, D, 2)), 3 * D.p, D),
-                             cx.st));
+  if (cx.bk->fused_attn) {
+    LYNX_LAUNCH(cx, kB6DVFused, lynx::attn_fused_bwd_dv(qkv, 3 * D.p, temp_ptr(cx, t_dc), D.p, attn_stats_ptr(cx), dqkv,
+                                                   3 * D.p, attn_shape(L), D.d, 1.0f / sqrtf(static_cast<float>(D.d)),
+                                                   dropout_params(L), cx.st));
+  } else {
+    LYNX_LAUNCH(cx, kB6DV, lynx::gemm(dt, attn_cols(act_ptr(cx, 5), temp_ptr(cx, t_dc), D.p,
+                                             const_cast<char*>(col_block(dqkv, D, 2)), 3 * D.p, D),
+                               cx.st));
+  }
   free_temp(cx, &t_dc);
   free_act(cx, 5);
   free_act(cx, 6);
-  if (!fused_ds) {
+  if (!fused_ds && !cx.bk->fused_attn) {
     LYNX_LAUNCH(cx, kB54Softmax, lynx::softmax_dropout_bwd(dt, temp_ptr(cx, t_dpd), act_ptr(cx, 4),
                                               temp_ptr(cx, t_dpd), attn_shape(L),
                                               1.0f / sqrtf(static_cast<float>(D.d)), dropout_params(L),

@@ -56,11 +56,8 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
     for (int k = 0; k < 8; ++k) z[c][k] = softmax_exp(z[c][k], m);
     float t0 = softmax_group4(z[c][0], z[c][1], z[c][2], z[c][3]);
     float t1 = softmax_group4(z[c][4], z[c][5], z[c][6], z[c][7]);
-#pragma unroll
-    for (int o = 1; o < 8; o <<= 1) {
-      t0 += __shfl_xor(t0, o, kWave);
-      t1 += __shfl_xor(t1, o, kWave);
-    }
+    t0 = group8_sum(t0);
+    t1 = group8_sum(t1);
     const float blk = t0 + t1;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {

@@ -99,6 +99,24 @@ def test_single_layer_full_size(name):
         for k, v in layer.grads.items():
             assert torch.equal(v, ref_grads[k]), (hex(mask), k)
     layer.close()
+    if name != "C4":
+        return
+    # the same with the attention that never stores S, P, Pd: same bits, smaller workspace
+    del layer
+    torch.cuda.empty_cache()
+    fcfg = cfg.with_(flags=1)
+    need_fused = B.lynx_workspace_bytes(fcfg, pm.FULL_RECOMPUTE)
+    assert need_fused < B.lynx_workspace_bytes(cfg, pm.FULL_RECOMPUTE) - 2 * B.lynx_activation_bytes(cfg, 4)
+    fused = GpuLayer(fcfg, params, workspace_bytes=need_fused)
+    fused.forward(X, pm.FULL_RECOMPUTE)
+    fused.backward(dOUT)
+    torch.cuda.synchronize()
+    assert B.lynx_layer_peak_bytes(fused.handle) <= need_fused
+    assert torch.equal(fused.out, ref_out)
+    assert torch.equal(fused.dx, ref_dx)
+    for k, v in fused.grads.items():
+        assert torch.equal(v, ref_grads[k]), k
+    fused.close()
 
 
 @pytest.mark.parametrize("l", range(synth.C5_LAYERS))

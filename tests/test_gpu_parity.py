@@ -116,15 +116,25 @@ def test_store_all_forward_and_backward_match_oracle(name):
 
 
 @pytest.mark.parametrize("name", ["C1", "ragged_bf16", "tiles_bf16", "tiles128_bf16", "tiles256_bf16", "long_seq_bf16",
-                                  "wide_bf16", "edge_bf16", "pair128_bf16", "ln_stream_bf16"])
+                                  "wide_bf16", "edge_bf16", "pair128_bf16", "ln_stream_bf16",
+                                  "tiles_bf16+fused", "tiles128_bf16+fused", "tiles256_bf16+fused",
+                                  "long_seq_bf16+fused", "edge_bf16+fused", "pair128_bf16+fused"])
 def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
-    cfg = SMALL[name]
+    """'+fused': the same layer with LYNX_FLAG_FUSED_ATTENTION: the store-all reference runs the
+    unfused kernels (it keeps S, P, Pd), every mask that drops the three runs the kernels that
+    never store them, and all results must still be the same bits."""
+    cfg = SMALL[name.split("+")[0]]
+    if name.endswith("+fused"):
+        cfg = cfg.with_(flags=1)
     params = synth.make_params(cfg, random_ln=True)
     X, dOUT = synth.make_x(cfg), synth.make_dout(cfg)
     from paper_2406_08756_amd import binding as B
     rng = np.random.default_rng(17)
     masks = [pm.FULL_RECOMPUTE, pm.ATTENTION_ONLY, pm.ELEMENTWISE_ONLY, 1]
     masks += [int(m) | 1 for m in rng.integers(0, 1 << 14, size=12)]
+    if cfg.flags & 1:
+        masks += [int(m) & ~0x38 | 1 for m in rng.integers(0, 1 << 14, size=6)]   # more masks that run fused
+        assert sum(pm.fused_attention(cfg, m) for m in masks) >= 8
     # every run starts from an empty workspace, so the exact size per mask applies to each
     layer = GpuLayer(cfg, params, workspace_bytes=max(B.lynx_workspace_bytes(cfg, m) for m in [pm.STORE_ALL] + masks))
 
@@ -156,7 +166,10 @@ def test_recompute_is_bit_identical_and_policy_does_not_change_results(name):
             layer.recompute(B.LYNX_SEG_ALL_MISSING)
             torch.cuda.synchronize()
             live = B.lynx_layer_live_mask(layer.handle)
-            for i in pm.BACKWARD_NEEDS:
+            fused = pm.fused_attention(cfg, mask)
+            if fused:
+                assert not live & 0x38, hex(mask)     # S, P, Pd never exist under such a policy
+            for i in pm.backward_needs(fused):
                 assert (live >> i) & 1
                 if i == 0:
                     continue

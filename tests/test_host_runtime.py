@@ -51,12 +51,17 @@ def test_activation_bytes_match_model():
         assert [B.lynx_activation_bytes(cfg, i) for i in range(14)] == M
 
 
-@pytest.mark.parametrize("name", ["C1", "C4"])
+@pytest.mark.parametrize("name", ["C1", "C4", "C4+fused"])
 def test_bookkeeping_matches_model_for_many_masks(name):
-    cfg = synth.CONFIGS[name]
+    cfg = synth.CONFIGS[name.split("+")[0]]
     rng = np.random.default_rng(5)
     masks = [pm.STORE_ALL, pm.FULL_RECOMPUTE, pm.ATTENTION_ONLY, pm.ELEMENTWISE_ONLY, 0]
     masks += [int(m) for m in rng.integers(0, 1 << 14, size=40)]
+    if name.endswith("+fused"):
+        # attention without the seq x seq tensors wherever the mask drops S, P and Pd
+        cfg = cfg.with_(flags=1)
+        masks += [int(m) & ~0x38 for m in rng.integers(0, 1 << 14, size=20)]
+        assert sum(pm.fused_attention(cfg, m) for m in masks) >= 20
     # explicit segments in arbitrary order can fragment the workspace beyond the
     # exact size of the canonical sequence, so this test is generous
     h = dry_layer(cfg, ws_bytes=2 * B.lynx_workspace_bytes(cfg, B.LYNX_RETAIN_STORE_ALL))
@@ -67,7 +72,7 @@ def test_bookkeeping_matches_model_for_many_masks(name):
         assert B.lynx_layer_live_mask(h) == model.live_mask()
         assert B.lynx_layer_live_bytes(h) == model.live_bytes()
         # split the regeneration into two explicit segments, then backward
-        ops = pm.missing_closure(set(model.live))
+        ops = pm.missing_closure(set(model.live), model.fused)
         half = len(ops) // 2
         for seg in (ops[:half], ops[half:]):
             m = sum(1 << i for i in seg)
