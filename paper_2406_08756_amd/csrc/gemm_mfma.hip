@@ -68,7 +68,7 @@ struct MfmaGemmArgs {
 };
 
 // One output tile: `block_x` selects the tile, `block_z` the matrix of a batch.
-template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, bool SPLITK = false>
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, bool SPLITK = false, int STAGES = kStages>
 __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block_x, const int block_z) {
   constexpr int WM = BM / 2, WN = BN / 2;  // wavefronts in a 2 x 2 grid
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -151,7 +151,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
 
   // j-th direct load of slab kt (A pieces first, then B) -> ring stage kt % kStages
   auto issue_load = [&](int kt, int j) {
-    bf16_t* sa = smem + (kt & (kStages - 1)) * kStageElems;
+    bf16_t* sa = smem + (kt % STAGES) * kStageElems;
     if (j < SA::kLoadsPerWave) {
       __builtin_amdgcn_global_load_lds((global_void_ptr)(ga[j] + kt * a_step),
                                        (lds_void_ptr)(sa + SA::lds_offset(wave, j)), 16, 0, 0);
@@ -176,11 +176,13 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (k_end - k_begin) / kBK;
-  // prologue: three slabs in flight, the first one landed
+  // prologue: STAGES - 1 slabs in flight, the first one landed
+  constexpr int kAhead = STAGES - 1;
+  static_assert(kAhead == 2 || kAhead == 3, "ring depth");
   issue_slab(0);
   if (nk > 1) issue_slab(1);
-  if (nk > 2) issue_slab(2);
-  if (nk > 2) wait_vmcnt<2 * kLoads>();
+  if (kAhead > 2 && nk > 2) issue_slab(2);
+  if (kAhead > 2 && nk > 2) wait_vmcnt<2 * kLoads>();
   else if (nk > 1) wait_vmcnt<kLoads>();
   else wait_vmcnt<0>();
   block_barrier();
@@ -200,7 +202,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
   // so the matrix pipe never waits for an issue burst: during the first half the
   // second-half fragments are read and the ring stage that every wavefront finished
   // before the last barrier is refilled; then [next slab landed?] [barrier]; during the
-  // second half the next slab's first-half fragments are read.  `steady` = three more
+  // second half the next slab's first-half fragments are read.  `steady` = STAGES - 1 more
   // slabs exist, so the refill and the waits need no conditions.
   constexpr int kMfmas = TM * TN;
   constexpr int kSide1 = TM + TN + kLoads;               // side operations of the first half
@@ -208,9 +210,9 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
   constexpr int kPer2 = (TM + TN + kMfmas - 1) / kMfmas;
   auto slab_step = [&](int kt, auto steady_tag) {
     constexpr bool steady = decltype(steady_tag)::value;
-    const bf16_t* sa = smem + (kt & (kStages - 1)) * kStageElems;
+    const bf16_t* sa = smem + (kt % STAGES) * kStageElems;
     const bf16_t* sb = sa + SA::kElems;
-    const bool refill = steady || kt + 3 < nk;
+    const bool refill = steady || kt + kAhead < nk;
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
       const int i = m / TM, j = m % TM;
@@ -220,14 +222,14 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
         const int op = m * kPer1 + u;
         if (op < TM) fa1[op] = SA::fragment(sa, wm0 + 32 * op, 1, lane);
         else if (op < TM + TN) fb1[op - TM] = SB::fragment(sb, wn0 + 32 * (op - TM), 1, lane);
-        else if (op < kSide1) { if (refill) issue_load(kt + 3, op - TM - TN); }
+        else if (op < kSide1) { if (refill) issue_load(kt + kAhead, op - TM - TN); }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     // the next slab must have landed (two newer ones may still be in flight), and all
     // of this wavefront's reads of the current slab must be complete
-    if (steady || kt + 3 < nk) wait_vmcnt<2 * kLoads>();
-    else if (kt + 2 < nk) wait_vmcnt<kLoads>();
+    if (steady || kt + kAhead < nk) wait_vmcnt<(kAhead - 1) * kLoads>();
+    else if (kAhead > 2 && kt + 2 < nk) wait_vmcnt<kLoads>();
     else wait_vmcnt<0>();
     wait_lgkmcnt0();
     block_barrier();
@@ -236,7 +238,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
 #pragma unroll
     for (int i = 0; i < TN; ++i) fb1[i].settle();
     const bool more = steady || kt + 1 < nk;
-    const bf16_t* na = smem + ((kt + 1) & (kStages - 1)) * kStageElems;
+    const bf16_t* na = smem + ((kt + 1) % STAGES) * kStageElems;
     const bf16_t* nb = na + SA::kElems;
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
@@ -266,7 +268,7 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
 #pragma unroll
   for (int i = 0; i < TN; ++i) fb0[i].settle();
   int kt = 0;
-  for (; kt + 3 < nk; ++kt) slab_step(kt, std::true_type{});
+  for (; kt + kAhead < nk; ++kt) slab_step(kt, std::true_type{});
   for (; kt < nk; ++kt) slab_step(kt, std::false_type{});
 
   // Epilogue.  acc[i][j][r] is the element n = wn0 + 32 i + 8 (r/4) + 4 (lane/32) + r%4,
@@ -406,6 +408,21 @@ __device__ __forceinline__ void gemm_tile(const MfmaGemmArgs& g, const int block
 template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN>
 __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(MfmaGemmArgs g) {
   gemm_tile<A_KMAJOR, B_KMAJOR, BM, BN>(g, blockIdx.x, blockIdx.y);
+}
+
+// 256 x 128 tiles with a three-stage ring (72 KB) and at most 256 registers, so that two
+// workgroups share a compute unit: for launches whose store pass is long (bias + dropout +
+// residual: one Philox call per 8 outputs, about as long as a 20-slab contraction), one
+// workgroup's store pass then runs on the vector ALUs while the other's contraction keeps
+// the matrix cores busy.
+constexpr int kDuoStages = 3;
+// contractions up to this length take the two-workgroup form (measured at the 13B shard: the
+// attention projection, K = 640, 0.198 -> 0.178 ms; FC2, K = 2560, 0.442 -> 0.461 ms: there the
+// larger tile's lower LDS and L2 traffic wins over the overlapped store pass)
+constexpr int kDuoMaxK = 1024;
+template <bool A_KMAJOR, bool B_KMAJOR>
+__global__ void __launch_bounds__(kThreads, 2) gemm_mfma_duo_kernel(MfmaGemmArgs g) {
+  gemm_tile<A_KMAJOR, B_KMAJOR, 256, 128, false, kDuoStages>(g, blockIdx.x, blockIdx.y);
 }
 
 // Score-shaped batched products with a short contraction (S = Q K^T, dPd = dC V^T: K = head
@@ -797,6 +814,17 @@ hipError_t launch(const MfmaGemmArgs& a, hipStream_t st) {
 }
 
 template <bool AK, bool BK_>
+hipError_t launch_duo(MfmaGemmArgs a, hipStream_t st) {
+  constexpr size_t smem = static_cast<size_t>(kDuoStages) * (256 + 128) * kBK * sizeof(bf16_t);
+  auto kern = gemm_mfma_duo_kernel<AK, BK_>;
+  LYNX_RAISE_LDS_LIMIT(kern, smem);
+  a.tiles_m = a.M / 256;
+  a.tiles_n = a.N / 128;
+  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n, a.nz), dim3(kThreads), smem, st, a);
+  return hipGetLastError();
+}
+
+template <bool AK, bool BK_>
 hipError_t launch_edge(const MfmaGemmArgs& a, hipStream_t st) {
   constexpr size_t smem = static_cast<size_t>(kStages) * (256 + 256) * kBK * sizeof(bf16_t);
   auto kern = gemm_mfma_edge_kernel<AK, BK_>;
@@ -857,6 +885,8 @@ hipError_t launch_tiles(MfmaGemmArgs a, hipStream_t st) {
     a.tiles_n = a.N / 128;
     return launch<AK, BK_, 128, 128>(a, st);
   }
+  if (a.epi == kEpiBiasDropoutAdd && a.nz == 1 && a.M % 256 == 0 && a.N % 128 == 0 && a.K <= kDuoMaxK)
+    return launch_duo<AK, BK_>(a, st);
   if (a.nz == 1 && a.M % 256 == 0 && a.N % 256 == 128 && (a.M / 256) * (a.N / 256 + 1) >= 128)
     return launch_edge<AK, BK_>(a, st);
   struct Cand { int bm, bn; float weight; };
