@@ -490,6 +490,24 @@ def main():
     B.lynx_layer_destroy(layer)
     cold = cold_measure(B, torch, cfg, params, x, out, stream) if args.cold else None
 
+    # What a plain device copy of one [T, h] tensor reaches on this machine, cold (four buffer
+    # pairs in rotation, 1.3 GB: past the 256 MB memory-side cache): the practical ceiling
+    # for the HBM-bound kernels, quoted beside each of them.
+    n_copy = cfg.tokens * cfg.hidden
+    pairs = [(torch.zeros(n_copy, dtype=tdtype, device="cuda"), torch.empty(n_copy, dtype=tdtype, device="cuda"))
+             for _ in range(4)]
+    for a, b in pairs:
+        b.copy_(a)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record(stream)
+    for rep in range(3):
+        for a, b in pairs:
+            b.copy_(a)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 12 * 2 * n_copy * x.element_size() / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del pairs
+
     work = slot_work(cfg)
     mfma_peak = PEAK_BF16_TFLOPS if cfg.dtype == synth.BF16 else PEAK_FP32_TFLOPS
     kernels = {}
@@ -505,10 +523,13 @@ def main():
         else:
             ach = amount / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "bound": "hbm", "achieved": round(ach, 1),
-                             "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4)}
-    log("%-28s %9s %6s %10s %8s" % ("kernel group", "ms", "bound", "achieved", "frac"))
+                             "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
+                             "frac_of_copy": round(ach / copy_gbs, 4)}
+    log("plain cold copy of one [T, h] tensor: %.1f GB/s (%.3f of 8 TB/s)" % (copy_gbs, copy_gbs / PEAK_HBM_GBS))
+    log("%-28s %9s %6s %10s %8s %8s" % ("kernel group", "ms", "bound", "achieved", "frac", "of copy"))
     for name, k in kernels.items():
-        log("%-28s %9.4f %6s %10.1f %8.3f" % (name, k["ms"], k["bound"], k["achieved"], k["frac"]))
+        log("%-28s %9.4f %6s %10.1f %8.3f %8s" % (name, k["ms"], k["bound"], k["achieved"], k["frac"],
+                                                   "%.3f" % k["frac_of_copy"] if "frac_of_copy" in k else ""))
 
     # dominant kernel: the dense linear-layer products (forward, dgrad, wgrad share
     # one kernel family); quote the one with the most time per step
@@ -548,6 +569,9 @@ def main():
         "algorithmic_tflop": {"forward": fwd_f / 1e12, "recompute": rec_f / 1e12, "backward": bwd_f / 1e12},
         "workspace_bytes": ws_bytes,
         "roofline": roofline,
+        "hbm_copy_ceiling": {"value": round(copy_gbs, 1), "unit": "GB/s", "frac": round(copy_gbs / PEAK_HBM_GBS, 4),
+                             "what": "torch copy_ of one [T, h] tensor, four buffer pairs in rotation (cold), "
+                                     "read + written bytes"},
         "kernels": kernels,
     }
     if overlap is not None:
