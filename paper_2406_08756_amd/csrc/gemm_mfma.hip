@@ -425,28 +425,51 @@ __global__ void __launch_bounds__(kThreads, 2) gemm_mfma_duo_kernel(MfmaGemmArgs
   gemm_tile<A_KMAJOR, B_KMAJOR, 256, 128, false, kDuoStages>(g, blockIdx.x, blockIdx.y);
 }
 
+// Work items of the score-shaped row-block kernels: row block tm (128 rows) owns tiles
+// tn = 0..tm; it is cut into runs of at most kAttnRun tiles, one workgroup each, so that no
+// workgroup walks more than kAttnRun tiles (a workgroup per whole row block leaves the launch
+// waiting for the 16-tile blocks while most compute units have run out of work).  Items are
+// numbered longest row block first; item * nz + z is the workgroup of matrix z.
+constexpr int kAttnRun = 4;
+__host__ __device__ inline int attn_runs_of(int tm) { return (tm + kAttnRun) / kAttnRun; }
+inline int attn_items(int tiles_m) {
+  int n = 0;
+  for (int tm = 0; tm < tiles_m; ++tm) n += attn_runs_of(tm);
+  return n;
+}
+// item -> (tm, first tile, one past the last tile)
+__device__ __forceinline__ void attn_item(int item, int tiles_m, int& tm, int& tn0, int& tn1) {
+  tm = tiles_m - 1;
+  while (tm > 0 && item >= attn_runs_of(tm)) {
+    item -= attn_runs_of(tm);
+    --tm;
+  }
+  tn0 = item * kAttnRun;
+  tn1 = min(tn0 + kAttnRun, tm + 1);
+}
+
 // Score-shaped batched products with a short contraction (S = Q K^T, dPd = dC V^T: K = head
 // dimension), lower triangle only.  A tile of such a product is all latency: load two small
-// operand tiles, 32 MFMAs per wavefront, store 32 KB.  Here a workgroup owns one block of
-// 128 rows of one matrix and walks its tiles tn = 0..tm: the A tile stays in LDS, the B tile
-// of the next step is fetched (direct to LDS, two buffers) while the current one is
-// multiplied and stored, and the stores are never waited for, so the kernel runs at the
-// rate its output can be written.  Row blocks are issued longest first.
+// operand tiles, 32 MFMAs per wavefront, store 32 KB.  Here a workgroup owns a run of tiles of
+// one block of 128 rows of one matrix: the A tile stays in LDS; the one B buffer doubles as
+// the staging area of the store pass, the next B tile is requested as soon as every wavefront
+// has its rows back in registers, and the stores are never waited for.  At 64 KB of LDS (head
+// dimension 128) two workgroups share a compute unit: one loads and stores while the other
+// multiplies.
 template <int KD>
-__global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
+__global__ void __launch_bounds__(kThreads, 2) attn_outer_kernel(MfmaGemmArgs g) {
   constexpr int WM = 64, WN = 64, TM = 2, TN = 2;
   constexpr int kSlabs = KD / kBK;
   using SL = Slab<128, true>;
   constexpr int kOpElems = kSlabs * SL::kElems;       // one 128 x KD operand tile
-  constexpr int kOpLoads = kSlabs * SL::kLoadsPerWave;  // direct loads per wavefront per tile
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);
-  bf16_t* sB = sA + kOpElems;                           // two buffers
-  bf16_t* sStage = sB + 2 * kOpElems;                   // 4 x (64 x 64)
+  bf16_t* sB = sA + kOpElems;                           // B tile, then 4 x (64 x 64) of staging
 
-  const int t = blockIdx.x / g.nz;
-  const int bz = blockIdx.x - t * g.nz;
-  const int tm = g.tiles_m - 1 - t;
+  const int item = blockIdx.x / g.nz;
+  const int bz = blockIdx.x - item * g.nz;
+  int tm, tn0, tn1;
+  attn_item(item, g.tiles_m, tm, tn0, tn1);
   const int z1 = bz / g.nz2, z2 = bz - z1 * g.nz2;
   const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2 + static_cast<long long>(tm) * 128 * g.lda;
   const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
@@ -471,22 +494,19 @@ __global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
                                          (lds_void_ptr)(dst + sl * SL::kElems + SL::lds_offset(wave, j)), 16, 0, 0);
   };
   load_tile(Abase, offA, sA);
-  load_tile(Bbase, offB, sB);
+  load_tile(Bbase + static_cast<long long>(tn0) * 128 * g.ldb, offB, sB);
 
   constexpr int kRowChunks = WN / 8;                    // 8
   constexpr int kRowsPerStore = kWave / kRowChunks;     // 8
   constexpr int kStores = WM / kRowsPerStore;           // 8 stores per wavefront per tile
-  bf16_t* stage = sStage + wave * (WM * WN);
+  bf16_t* stage = sB + wave * (WM * WN);
   const int lr = lane / kRowChunks, lc = lane % kRowChunks;
 
-  for (int tn = 0; tn <= tm; ++tn) {
-    // B(tn) (and, the first time, A) has landed: everything older than the previous tile's
-    // stores.  The barrier also says every wavefront has finished reading B(tn - 1).
-    if (tn == 0) wait_vmcnt<0>();
+  for (int tn = tn0; tn < tn1; ++tn) {
+    // B(tn) (and, the first time, A) has landed: everything older than the previous tile's stores
+    if (tn == tn0) wait_vmcnt<0>();
     else wait_vmcnt<kStores>();
     block_barrier();
-    if (tn < tm) load_tile(Bbase + static_cast<long long>(tn + 1) * 128 * g.ldb, offB, sB + ((tn + 1) & 1) * kOpElems);
-    const bf16_t* sb = sB + (tn & 1) * kOpElems;
 
     floatx16_t acc[TN][TM];
 #pragma unroll
@@ -501,14 +521,15 @@ __global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
 #pragma unroll
       for (int j = 0; j < TM; ++j) fa[j] = SL::fragment(sA + (kk >> 1) * SL::kElems, wm0 + 32 * j, kk & 1, lane);
 #pragma unroll
-      for (int i = 0; i < TN; ++i) fb[i] = SL::fragment(sb + (kk >> 1) * SL::kElems, wn0 + 32 * i, kk & 1, lane);
+      for (int i = 0; i < TN; ++i) fb[i] = SL::fragment(sB + (kk >> 1) * SL::kElems, wn0 + 32 * i, kk & 1, lane);
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i].operand(), fa[j].operand(), acc[i][j], 0, 0, 0);
     }
-    // round into this wavefront's staging region, then whole rows out, 16 bytes per lane
+    block_barrier();  // every wavefront has read B(tn): its buffer becomes the staging area
+    // round into this wavefront's staging region, then whole rows back, 16 bytes per lane
     // (acc[i][j][r]: n = wn0 + 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4, m = wm0 + 32 j + lane % 32)
 #pragma unroll
     for (int i = 0; i < TN; ++i)
@@ -523,16 +544,15 @@ __global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
           o[1] = pack_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
           const int chunk = (nl >> 3) ^ (ml & (kRowChunks - 1));
           // As inline assembly: a store to LDS that the compiler sees is made to wait for
-          // every direct-to-LDS load in flight (here: the next B tile) and, with them, for
-          // the previous tile's stores.  LDS executes a wavefront's accesses in order, so
-          // the row reads below see these writes.
+          // every direct-to-LDS load in flight and, with them, for the previous tile's
+          // stores.  LDS executes a wavefront's accesses in order, so the row reads below
+          // see these writes.
           typedef __attribute__((address_space(3))) bf16_t* lds_ptr_t;
           const uint32_t addr = static_cast<uint32_t>(
               reinterpret_cast<uintptr_t>((lds_ptr_t)(stage + ml * WN + chunk * 8 + (nl & 7))));
           asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(o) : "memory");
         }
       }
-    bf16_t* cw = Cbase + static_cast<long long>(wm0) * g.ldc + tn * 128 + wn0;
     uintx4_t rows[kStores];
 #pragma unroll
     for (int u = 0; u < kStores; ++u) {
@@ -544,8 +564,12 @@ __global__ void __launch_bounds__(kThreads) attn_outer_kernel(MfmaGemmArgs g) {
     }
     wait_lgkmcnt0();
 #pragma unroll
+    for (int u = 0; u < kStores; ++u) asm volatile("" : "+v"(rows[u]));
+    block_barrier();  // every wavefront has its rows: the buffer can take the next B tile
+    if (tn + 1 < tn1) load_tile(Bbase + static_cast<long long>(tn + 1) * 128 * g.ldb, offB, sB);
+    bf16_t* cw = Cbase + static_cast<long long>(wm0) * g.ldc + tn * 128 + wn0;
+#pragma unroll
     for (int u = 0; u < kStores; ++u) {
-      asm volatile("" : "+v"(rows[u]));
       const int r = u * kRowsPerStore + lr;
       *reinterpret_cast<uintx4_t*>(cw + static_cast<long long>(r) * g.ldc + lc * 8) = rows[u];
     }
@@ -575,9 +599,10 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
   bf16_t* sB = sA + kOpElems;
   static_assert(kOpElems >= 4 * WM * WN || KD < 128, "staging fits the B buffer");
 
-  const int t = blockIdx.x / g.nz;
-  const int bz = blockIdx.x - t * g.nz;
-  const int tm = g.tiles_m - 1 - t;
+  const int item = blockIdx.x / g.nz;
+  const int bz = blockIdx.x - item * g.nz;
+  int tm, tn0, tn1;
+  attn_item(item, g.tiles_m, tm, tn0, tn1);
   const int z1 = bz / g.nz2, z2 = bz - z1 * g.nz2;
   const bf16_t* Abase = g.A + z1 * g.a_z1 + z2 * g.a_z2 + static_cast<long long>(tm) * 128 * g.lda;
   const bf16_t* Bbase = g.B + z1 * g.b_z1 + z2 * g.b_z2;
@@ -603,7 +628,7 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
   };
   constexpr int kTileLoads = kSlabs * SL::kLoadsPerWave;  // direct loads per wavefront per tile
   load_tile(Abase, offA, sA);
-  load_tile(Bbase, offB, sB);
+  load_tile(Bbase + static_cast<long long>(tn0) * 128 * g.ldb, offB, sB);
 
   constexpr int kRowChunks = WN / 8;                 // 8
   constexpr int kRowsPerStore = kWave / kRowChunks;  // 8
@@ -624,7 +649,7 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
       asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(pv[u]) : "v"(src) : "memory");
     }
   };
-  request_p(0, p0);
+  request_p(tn0, p0);
 #pragma unroll
   for (int u = 0; u < kStores; ++u) {
     const int i = tm * 128 + wm0 + u * kRowsPerStore + lr;
@@ -639,7 +664,7 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
   auto tile_step = [&](const int tn, uintx4_t (&pc)[kStores], uintx4_t (&pn)[kStores]) {
     // B(tn) has landed.  Issued after it: the previous step's requests for P and its stores
     // (nothing the first time, when everything issued so far is waited for).
-    if (tn == 0) wait_vmcnt<0>();
+    if (tn == tn0) wait_vmcnt<0>();
     else wait_vmcnt<2 * kStores>();
     block_barrier();
     floatx16_t acc[TN][TM];
@@ -696,15 +721,15 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
 #pragma unroll
     for (int u = 0; u < kStores; ++u) asm volatile("" : "+v"(rows[u]));
     block_barrier();  // every wavefront has its rows: the buffer can take the next B tile
-    if (tn < tm) {
+    if (tn + 1 < tn1) {
       load_tile(Bbase + static_cast<long long>(tn + 1) * 128 * g.ldb, offB, sB);
       request_p(tn + 1, pn);
     }
     // this tile's P: requested a step ago; issued since: the previous step's stores and, if
     // there is a next tile, its B tile and its P
-    if (tn == 0) {
+    if (tn == tn0) {
       // (waited for at the top)
-    } else if (tn < tm) {
+    } else if (tn + 1 < tn1) {
       wait_vmcnt<2 * kStores + kTileLoads>();
     } else {
       wait_vmcnt<kStores>();
@@ -727,9 +752,9 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
     }
   };
   // two tiles per trip, so the two sets of P registers swap roles without being copied
-  for (int tn = 0; tn <= tm; tn += 2) {
+  for (int tn = tn0; tn < tn1; tn += 2) {
     tile_step(tn, p0, p1);
-    if (tn + 1 <= tm) tile_step(tn + 1, p1, p0);
+    if (tn + 1 < tn1) tile_step(tn + 1, p1, p0);
   }
 }
 
@@ -846,12 +871,14 @@ hipError_t launch_edge(const MfmaGemmArgs& a, hipStream_t st) {
 
 template <int KD>
 hipError_t launch_attn_outer(MfmaGemmArgs a, hipStream_t st) {
-  constexpr size_t smem = (3 * static_cast<size_t>(KD / kBK) * 128 * kBK + 4 * 64 * 64) * sizeof(bf16_t);
+  // A tile + the B tile / staging area (4 x 64 x 64, the larger of the two for short head dimensions)
+  constexpr size_t op = static_cast<size_t>(KD / kBK) * 128 * kBK;
+  constexpr size_t smem = (op + (op > 4 * 64 * 64 ? op : 4 * 64 * 64)) * sizeof(bf16_t);
   auto kern = attn_outer_kernel<KD>;
   LYNX_RAISE_LDS_LIMIT(kern, smem);
   a.tiles_m = a.M / 128;
   a.tiles_n = a.N / 128;
-  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.nz), dim3(kThreads), smem, st, a);
+  hipLaunchKernelGGL(kern, dim3(attn_items(a.tiles_m) * a.nz), dim3(kThreads), smem, st, a);
   return hipGetLastError();
 }
 
@@ -862,7 +889,7 @@ hipError_t launch_attn_dscores(MfmaGemmArgs a, hipStream_t st) {
   LYNX_RAISE_LDS_LIMIT(kern, smem);
   a.tiles_m = a.M / 128;
   a.tiles_n = a.N / 128;
-  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.nz), dim3(kThreads), smem, st, a);
+  hipLaunchKernelGGL(kern, dim3(attn_items(a.tiles_m) * a.nz), dim3(kThreads), smem, st, a);
   return hipGetLastError();
 }
 
