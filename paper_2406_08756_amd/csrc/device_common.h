@@ -49,6 +49,19 @@ __device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
   *reinterpret_cast<uint4*>(p) = r;
 }
 
+// The same stores with the streaming hint: for a tensor nothing reads again soon, so that it
+// does not push a tensor the next kernel reads out of the caches.
+typedef unsigned int uint32x4_t __attribute__((ext_vector_type(4)));
+typedef float float32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store8_streaming(float* p, const float (&v)[8]) {
+  __builtin_nontemporal_store(float32x4_t{v[0], v[1], v[2], v[3]}, reinterpret_cast<float32x4_t*>(p));
+  __builtin_nontemporal_store(float32x4_t{v[4], v[5], v[6], v[7]}, reinterpret_cast<float32x4_t*>(p + 4));
+}
+__device__ __forceinline__ void store8_streaming(bf16_t* p, const float (&v)[8]) {
+  const uint32x4_t r = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+  __builtin_nontemporal_store(r, reinterpret_cast<uint32x4_t*>(p));
+}
+
 // 8 storage elements as loaded, before conversion (keeps loads cheap to batch).
 template <typename T> struct Raw8;
 template <> struct Raw8<bf16_t> { uint4 v; };

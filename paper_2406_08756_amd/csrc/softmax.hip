@@ -73,7 +73,11 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
       float pr[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) pr[k] = softmax_prob<T>(z[c][k], inv);
-      if (P != nullptr) store8(P + row + j0, pr);
+      if (P != nullptr) {
+        // with Pd also written, the next kernel (Pd V) reads Pd; P waits for backward
+        if (Pd != nullptr) store8_streaming(P + row + j0, pr);
+        else store8(P + row + j0, pr);
+      }
       if (Pd != nullptr) {
         // entries beyond the diagonal are exactly 0 already; the zero padding needs no draw
         if (j0 < nvalid) dropout_apply8(key, (gidx + j0) >> 3, pr);
