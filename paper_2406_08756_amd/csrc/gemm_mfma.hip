@@ -646,7 +646,7 @@ __global__ void __launch_bounds__(kThreads, 2) attn_dscores_kernel(MfmaGemmArgs 
 #pragma unroll
     for (int u = 0; u < kStores; ++u) {
       const bf16_t* src = Pw + static_cast<long long>(u * kRowsPerStore + lr) * g.ldc + tn * 128;
-      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(pv[u]) : "v"(src) : "memory");
+      asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(pv[u]) : "v"(src) : "memory");
     }
   };
   request_p(tn0, p0);
