@@ -82,6 +82,25 @@ __device__ __forceinline__ void unpack(const Raw8<float>& r, float (&v)[8]) {
   v[4] = r.hi.x; v[5] = r.hi.y; v[6] = r.hi.z; v[7] = r.hi.w;
 }
 
+// Loads with the non-temporal hint, for a tensor the kernel reads once and nothing reads again
+// soon: the lines do not displace what the next kernel will want from the caches.
+__device__ __forceinline__ void load_raw_streaming(const bf16_t* p, Raw8<bf16_t>& r) {
+  const uint32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const uint32x4_t*>(p));
+  r.v = make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void load_raw_streaming(const float* p, Raw8<float>& r) {
+  const float32x4_t a = __builtin_nontemporal_load(reinterpret_cast<const float32x4_t*>(p));
+  const float32x4_t b = __builtin_nontemporal_load(reinterpret_cast<const float32x4_t*>(p + 4));
+  r.lo = make_float4(a[0], a[1], a[2], a[3]);
+  r.hi = make_float4(b[0], b[1], b[2], b[3]);
+}
+template <typename T>
+__device__ __forceinline__ void load8_streaming(const T* p, float (&v)[8]) {
+  Raw8<T> r;
+  load_raw_streaming(p, r);
+  unpack(r, v);
+}
+
 // Makes the compiler forget what it derived from r, so values unpacked from it earlier are
 // recomputed from the (smaller) storage form instead of being kept in registers.
 __device__ __forceinline__ void forget(Raw8<bf16_t>& r) {

@@ -19,7 +19,7 @@ __global__ void __launch_bounds__(kThreads) gelu_fwd_kernel(const T* __restrict_
   const size_t v = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (v >= nvec) return;
   float x[8];
-  load8(u + v * 8, x);
+  load8_streaming(u + v * 8, x);
 #pragma unroll
   for (int i = 0; i < 8; ++i) x[i] = gelu_f(x[i]);
   store8(g + v * 8, x);
@@ -88,8 +88,8 @@ rows_colsum_kernel(Op op, const T* __restrict__ in0, const T* __restrict__ in1, 
       const int r = r0 + k * (kThreads / kWave);
       if (r < rows) {
         const size_t off = static_cast<size_t>(r) * cols + static_cast<size_t>(vec) * 8;
-        load_raw(in0 + off, ra[k]);
-        if (Op::kInputs == 2) load_raw(in1 + off, rb[Op::kInputs == 2 ? k : 0]);
+        load_raw_streaming(in0 + off, ra[k]);
+        if (Op::kInputs == 2) load_raw_streaming(in1 + off, rb[Op::kInputs == 2 ? k : 0]);
       }
     }
 #pragma unroll

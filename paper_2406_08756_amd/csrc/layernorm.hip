@@ -112,7 +112,7 @@ layernorm_fwd_stream_kernel(const T* __restrict__ x, const T* __restrict__ gamma
   if (first < per_xcd) {
     const size_t base = static_cast<size_t>(xcd_row0 + first) * cols;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) load_raw(x + base + j0[c], cur[c]);
+    for (int c = 0; c < NC; ++c) load_raw_streaming(x + base + j0[c], cur[c]);
   }
   for (int i = first; i < per_xcd; i += groups) {
     const int r = xcd_row0 + i;
@@ -120,7 +120,7 @@ layernorm_fwd_stream_kernel(const T* __restrict__ x, const T* __restrict__ gamma
     if (more) {
       const size_t nbase = static_cast<size_t>(r + groups) * cols;
 #pragma unroll
-      for (int c = 0; c < NC; ++c) load_raw(x + nbase + j0[c], nxt[c]);
+      for (int c = 0; c < NC; ++c) load_raw_streaming(x + nbase + j0[c], nxt[c]);
     }
     float v[NC][8];
     float sum = 0.f;
@@ -228,9 +228,15 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
       for (int c = 0; c < NC; ++c) {
         const int j0 = (threadIdx.x + c * kBwdThreads) * 8;
         if (j0 < cols) {
-          load_raw(dy + base + j0, rdy[q][c]);
-          load_raw(x + base + j0, rx[q][c]);
-          load_raw(dres + base + j0, rdr[q][c]);
+          if (DROP) {
+            load_raw(dy + base + j0, rdy[q][c]);
+            load_raw(x + base + j0, rx[q][c]);
+            load_raw(dres + base + j0, rdr[q][c]);
+          } else {
+            load_raw_streaming(dy + base + j0, rdy[q][c]);
+            load_raw_streaming(x + base + j0, rx[q][c]);
+            load_raw_streaming(dres + base + j0, rdr[q][c]);
+          }
         }
       }
     }

@@ -35,7 +35,7 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
   for (int c = 0; c < NC; ++c) {
     const int j0 = (lane + c * kWave) * 8;
     if (j0 < nvalid) {
-      load8(S + row + j0, z[c]);
+      load8_streaming(S + row + j0, z[c]);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         z[c][k] = (j0 + k < nvalid) ? softmax_logit(z[c][k], scale) : -INFINITY;
@@ -178,8 +178,8 @@ attn_rowdot_kernel(const T* __restrict__ x, const T* __restrict__ y, float* __re
     const size_t base = static_cast<size_t>(t) * ld + static_cast<size_t>(hd) * d;
     for (int v = l; v * 8 < d; v += 16) {
       float xv[8], yv[8];
-      load8(x + base + v * 8, xv);
-      load8(y + base + v * 8, yv);
+      load8(x + base + v * 8, xv);            // dC: the kernels that follow read it again
+      load8_streaming(y + base + v * 8, yv);  // C: its last use
 #pragma unroll
       for (int k = 0; k < 8; ++k) acc += xv[k] * yv[k];
     }
