@@ -26,13 +26,16 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
   const size_t row = (static_cast<size_t>(bh) * s + i) * s;
   const uint64_t gidx = ((static_cast<uint64_t>(bi) * global_heads + head0 + hd) * s + i) *
                         static_cast<uint64_t>(s);
-  const int nvalid = i + 1;
+  // (uniform over the wavefront: passes c whose 512 columns lie beyond the row are skipped as a
+  // whole; they would contribute exact zeros to the sum and nothing to the output)
+  const int nvalid = __builtin_amdgcn_readfirstlane(i + 1);
   const int npad = min(s, (nvalid + kPad - 1) / kPad * kPad);
 
   float z[NC][8];
   float m = -INFINITY;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
+    if (c * kWave * 8 >= nvalid) break;
     const int j0 = (lane + c * kWave) * 8;
     if (j0 < nvalid) {
       load8_streaming(S + row + j0, z[c]);
@@ -52,6 +55,7 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
   float a0 = 0.f, a1 = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
+    if (c * kWave * 8 >= nvalid) break;
 #pragma unroll
     for (int k = 0; k < 8; ++k) z[c][k] = softmax_exp(z[c][k], m);
     float t0 = softmax_group4(z[c][0], z[c][1], z[c][2], z[c][3]);
@@ -68,6 +72,7 @@ softmax_dropout_fwd_kernel(const T* __restrict__ S, T* __restrict__ P, T* __rest
   const float inv = softmax_inverse(a0 + a1);
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
+    if (c * kWave * 8 >= nvalid) break;
     const int j0 = (lane + c * kWave) * 8;
     if (j0 < npad) {
       float pr[8];
