@@ -520,6 +520,14 @@ def main():
             ach = amount / (ms * 1e-3) / 1e12
             kernels[name] = {"ms": round(ms, 4), "bound": "mfma", "achieved": round(ach, 2),
                              "unit": "TFLOP/s", "frac": round(ach / mfma_peak, 4)}
+            # the attention products move one seq x seq tensor (the causal triangle) for a contraction
+            # of only head_dim: they sit on the HBM side of the ridge, so quote them against it too
+            if name.split("/")[-1] in ("op3_scores", "op6_context", "b6_dpd", "b6_dv", "b3_dq", "b3_dk"):
+                tri_bytes = cfg.micro_batch * cfg.local_heads * cfg.seq * (cfg.seq + 1) // 2 * x.element_size()
+                gbs = tri_bytes / (ms * 1e-3) / 1e9
+                kernels[name].update({"hbm_achieved": round(gbs, 1), "hbm_unit": "GB/s of the causal triangle",
+                                      "hbm_frac": round(gbs / PEAK_HBM_GBS, 4),
+                                      "frac_of_copy": round(gbs / copy_gbs, 4)})
         else:
             ach = amount / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 4), "bound": "hbm", "achieved": round(ach, 1),
