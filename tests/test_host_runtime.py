@@ -174,3 +174,16 @@ def test_bad_arguments():
         B.lynx_layer_forward(h, FX, FOUT, 1 << 14, 0)
     assert e.value.status == B.LYNX_ERR_INVALID_ARG
     B.lynx_layer_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The measurement script is for one GPU: any other count ends with a message, before
+    anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
