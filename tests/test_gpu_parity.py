@@ -334,6 +334,49 @@ def test_regeneration_on_a_side_stream_under_the_comm_standin_keeps_the_bits(nam
     layer.close()
 
 
+def test_two_handles_from_two_host_threads_are_independent():
+    """Distinct handles share nothing: two layers of different shapes, each driven by its own
+    host thread on its own stream (forward under full recomputation, regeneration, backward,
+    several times over), end with the bits of the same calls made one after the other."""
+    import threading
+    from paper_2406_08756_amd import binding as B
+    names = ["tiles_bf16", "edge_bf16"]
+    layers, refs = [], []
+    for name in names:
+        cfg = SMALL[name]
+        layer = GpuLayer(cfg, synth.make_params(cfg, random_ln=True))
+        layer.forward(synth.make_x(cfg), pm.FULL_RECOMPUTE, step=3)
+        layer.backward(synth.make_dout(cfg))
+        torch.cuda.synchronize()
+        refs.append((layer.out.clone(), layer.dx.clone(), {k: v.clone() for k, v in layer.grads.items()}))
+        layers.append(layer)
+    errors = []
+
+    def drive(layer, ref):
+        try:
+            st = torch.cuda.Stream()
+            st.wait_stream(torch.cuda.default_stream())
+            for rep in range(4):
+                B.lynx_layer_forward(layer.handle, layer.x, layer.out, pm.FULL_RECOMPUTE, 3, st)
+                B.lynx_recompute(layer.handle, B.LYNX_SEG_ALL_MISSING, st)
+                B.lynx_layer_backward(layer.handle, layer.dout, layer.dx, layer.grads, st)
+                st.synchronize()
+                if not (torch.equal(layer.out, ref[0]) and torch.equal(layer.dx, ref[1])
+                        and all(torch.equal(v, ref[2][k]) for k, v in layer.grads.items())):
+                    errors.append(rep)
+        except Exception as exc:   # surfaced by the assert below
+            errors.append(repr(exc))
+
+    threads = [threading.Thread(target=drive, args=(l, r)) for l, r in zip(layers, refs)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for layer in layers:
+        layer.close()
+    assert errors == []
+
+
 def test_comm_standin_copies_and_checks_arguments():
     from paper_2406_08756_amd import binding as B
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
