@@ -571,7 +571,7 @@ __global__ void __launch_bounds__(kThreads, 2) attn_outer_kernel(MfmaGemmArgs g)
 #pragma unroll
     for (int u = 0; u < kStores; ++u) {
       const int r = u * kRowsPerStore + lr;
-      *reinterpret_cast<uintx4_t*>(cw + static_cast<long long>(r) * g.ldc + lc * 8) = rows[u];
+      __builtin_nontemporal_store(rows[u], reinterpret_cast<uintx4_t*>(cw + static_cast<long long>(r) * g.ldc + lc * 8));
     }
   }
 }
