@@ -230,8 +230,8 @@ layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
         if (j0 < cols) {
           if (DROP) {
             load_raw(dy + base + j0, rdy[q][c]);
-            load_raw(x + base + j0, rx[q][c]);
-            load_raw(dres + base + j0, rdr[q][c]);
+            load_raw_streaming(x + base + j0, rx[q][c]);
+            load_raw_streaming(dres + base + j0, rdr[q][c]);
           } else {
             load_raw_streaming(dy + base + j0, rdy[q][c]);
             load_raw_streaming(x + base + j0, rx[q][c]);
