@@ -29,9 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Not measured live:
 # counters need the profiler around the process.
 MEASURED_TRAFFIC_BYTES = {("C4", "full"): {
-    "b12_fc2_dgrad_wgrad": 2300.5e6, "b10_fc1_dgrad_wgrad": 2207.6e6, "b2_qkv_dgrad_wgrad": 2099.4e6,
-    "b7_proj_dgrad_wgrad": 1334.8e6, "op10_fc1_gemm": 809.0e6, "op12_fc2_gemm": 1009.7e6,
-    "op2_qkv_gemm": 668.2e6, "op7_attn_proj_gemm": 545.0e6}}
+    "b12_fc2_dgrad_wgrad": 2297.5e6, "b10_fc1_dgrad_wgrad": 2131.0e6, "b2_qkv_dgrad_wgrad": 2101.5e6,
+    "b7_proj_dgrad_wgrad": 1240.0e6, "op10_fc1_gemm": 809.0e6, "op12_fc2_gemm": 1009.7e6,
+    "op2_qkv_gemm": 664.8e6, "op7_attn_proj_gemm": 545.2e6}}
 
 POLICIES = {"store_all": 0x3FFF, "full": 0x2001, "attention_only": 0x3FFF & ~0x0038,
             "elementwise_only": 0x3FFF & ~0x0830}
